@@ -1,0 +1,176 @@
+/*
+ * adacomp.h -- C ABI of libadacomp: AdaComp residual-gradient compression on one AMD MI355X
+ * (gfx950).  Hand-written HIP kernels; no CPU fallback exists: without a GPU every compute
+ * entry point returns ADACOMP_EHIP.
+ *
+ * The method is that of "AdaComp: Adaptive Residual Gradient Compression for Data-Parallel
+ * Distributed Training" (arXiv 1712.02679).  Per learner and per mini-batch, pack() (Algorithm 2)
+ * adds the new gradient dW to the residue (G = residue + dW), forms H = G + dW, cuts every
+ * layer's flat vector into bins of length L_T, finds each bin's largest |G| (g_max), sends the
+ * elements whose |H| reaches their bin's g_max (together with the bin maximum itself, section
+ * "Adaptive Residual Gradient Compression (AdaComp) Technique"), quantises every sent value to
+ * sign(G) * scale with one scale per layer = average of the g_max vector (section "Pseudo
+ * code"), and keeps G - Gq (sent) or G (not sent) as the new residue.  Sent values travel as
+ * sparse-index words, 8 bits for L_T <= 64 and 16 bits up to L_T = 16384, two bits of which hold
+ * the ternary value (section "Experiment Results").  unpack() (Algorithm 1) decodes the packets a
+ * learner received; here it also sums them into one dense gradient.
+ *
+ * Conventions
+ *   - Pointers are DEVICE pointers unless the comment says host.  The library allocates and
+ *     frees no caller memory; the caller owns every buffer, including the workspace.
+ *   - Work is enqueued on the HIP stream passed in (a hipStream_t cast to void*, NULL = the
+ *     default stream) and the call returns without synchronising.  Results, including the packet
+ *     header, are in device memory once the stream has drained.
+ *   - Calls that share a workspace must be ordered on one stream; calls on different streams
+ *     need different workspaces.
+ *   - Every function returns 0 (ADACOMP_OK) or a negative ADACOMP_E* code; nothing throws or
+ *     aborts.  Inputs must be finite; NaN / Inf give unspecified values but stay memory-safe.
+ *   - Arithmetic is IEEE float32 with round-to-nearest-even and denormals kept; the layer scale
+ *     is summed and divided in float64 and rounded once.
+ *
+ * Packet container written by adacomp_compress (little-endian, offsets in bytes from the packet
+ * start, every padding byte zero, every section start a multiple of 16):
+ *
+ *   adacomp_packet_header_t                      32 bytes
+ *   adacomp_packet_layer_t[n_layers]             64 bytes each
+ *   per layer, in order:  counts[n_bins]  (uint8 when word_bits == 8, else uint16), pad to 16
+ *                         chunks[ceil(n_bins / 64)] uint32, pad to 16
+ *        counts[b] = words contributed by bin b; chunks[c] = words of this layer in bins < 64 c
+ *   per layer, in order:  words[n_selected] (uint8 | uint16), pad to 16
+ *        word = (index_in_bin << 2) | code;  code 1 = +scale, code 3 = -scale (2-bit two's
+ *        complement of the ternary value; 0 and 2 never occur); words are ordered by bin, then by
+ *        index inside the bin.
+ *   Compression rate by the paper's accounting = 32 * n_elems / (word_bits * n_selected);
+ *   on the wire = 4 * n_elems / total_bytes.
+ */
+#ifndef ADACOMP_H
+#define ADACOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADACOMP_OK 0
+#define ADACOMP_EINVAL (-1)     /* null pointer, n_layers == 0, n_elems == 0 or >= 2^31, overlapping layers */
+#define ADACOMP_EBADLT (-2)     /* L_T == 0 or L_T > 16384                                               */
+#define ADACOMP_EALIGN (-3)     /* elem_offset not a multiple of 4, or a buffer not 16-byte aligned      */
+#define ADACOMP_ENOSPC (-4)     /* packet_capacity below the fixed part of the packet                    */
+#define ADACOMP_EHIP (-5)       /* a HIP call failed (no device, launch failure)                         */
+#define ADACOMP_EWORKSPACE (-6) /* workspace too small, or not initialised for this layer table          */
+
+#define ADACOMP_LT_MAX 16384u
+#define ADACOMP_CHUNK_BINS 64u
+#define ADACOMP_PACKET_MAGIC 0x50434441u /* bytes 'A' 'D' 'C' 'P' */
+#define ADACOMP_PACKET_VERSION 1u
+#define ADACOMP_STATUS_COMPLETE 0u
+#define ADACOMP_STATUS_TRUNCATED 1u /* capacity was too small: words beyond it were not written */
+
+/* One layer of the flat gradient ("AdaComp is applied to every layer separately"; L_T is the
+ * paper's one hyper-parameter, per layer type: 50 for convolutions, 500 for FC / LSTM). */
+typedef struct {
+    uint64_t elem_offset; /* first element in grad / residue / dense_out; multiple of 4        */
+    uint64_t n_elems;     /* 1 .. 2^31-1; need not be a multiple of L_T (the last bin is short) */
+    uint32_t L_T;         /* bin length, 1 .. 16384                                             */
+    uint32_t reserved;    /* 0                                                                  */
+} adacomp_layer_t;
+
+typedef struct {
+    uint32_t magic, version, status, n_layers;
+    uint64_t total_bytes; /* size of the complete packet (what a transport has to move)   */
+    uint64_t n_selected;  /* words in all layers                                           */
+} adacomp_packet_header_t;
+
+typedef struct {
+    uint64_t elem_offset, n_elems;
+    uint32_t L_T, n_bins, word_bits; /* 8 or 16 */
+    float scale;                     /* decoded magnitude of every word of this layer */
+    uint64_t n_selected;
+    uint64_t counts_offset, chunks_offset, words_offset;
+} adacomp_packet_layer_t;
+
+/* ---- sizes (host-only arithmetic; layers is a host array) ---------------------------------- */
+
+/* Bytes of a packet in which every element of every layer is sent: a capacity that can never
+ * overflow.  Returns 0 if the layer table is invalid. */
+size_t adacomp_packet_bound(const adacomp_layer_t *layers, uint32_t n_layers);
+
+/* Bytes before the first word (header, records, counts, chunks): the least capacity accepted. */
+size_t adacomp_packet_fixed_bytes(const adacomp_layer_t *layers, uint32_t n_layers);
+
+/* Bytes of workspace adacomp_workspace_init / compress / unpack need for this table (device
+ * tables, per-bin g_max, per-tile counters, staging for unplaced words). 0 if the table is invalid. */
+size_t adacomp_workspace_bytes(const adacomp_layer_t *layers, uint32_t n_layers);
+
+/* ---- set-up --------------------------------------------------------------------------------- */
+
+/* Writes the device-side tile tables for this layer table into the head of `workspace`
+ * (256-byte aligned device memory of at least adacomp_workspace_bytes()).  Call once per
+ * workspace and layer table, before the first compress / unpack that uses it.  The tables are
+ * copied with a blocking host-to-device copy ordered after the work already on `hip_stream`, so
+ * this call is not capturable in a HIP graph; compress and unpack only launch kernels.  The
+ * caller must leave the workspace contents alone between calls. */
+int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
+/* Forgets a workspace registered by adacomp_workspace_init (host bookkeeping only). */
+int adacomp_workspace_release(void *workspace);
+
+/* ---- pack(): Algorithm 2 over every layer of one learner ------------------------------------- */
+
+/* grad       dW of this mini-batch, read only; 16-byte aligned; layers at their elem_offset.
+ * residue    in: residue carried from the previous mini-batch (zeros at the start of training);
+ *            out: the new residue.  Must not alias grad.
+ * packet_out receives the packet; 16-byte aligned.  packet_capacity >= adacomp_packet_fixed_bytes
+ *            or ADACOMP_ENOSPC is returned and nothing is enqueued.  If the words do not fit,
+ *            header.status = ADACOMP_STATUS_TRUNCATED, header.total_bytes is the size that was
+ *            needed, no byte past packet_capacity is written, and the residue is updated as if
+ *            everything had been sent (the packet must then be discarded by the caller).
+ * Elements of grad / residue outside every layer are neither read nor written. */
+int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
+                     float *residue, void *packet_out, size_t packet_capacity, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
+
+/* ---- unpack() of all learners, summed ("unpack()" then the sum inside "averageGradients()") -- */
+
+/* packets    HOST array of n_learners DEVICE pointers to complete packets made by
+ *            adacomp_compress with the same layer table.  A packet whose header does not match
+ *            (magic, version, status, n_layers) contributes nothing.
+ * dense_out  every element of every layer is overwritten with the float32 sum, taken in learner
+ *            order 0..n-1, of the decoded values (+-scale of that learner's layer where it sent
+ *            the element, 0 elsewhere); 16-byte aligned.  n_learners == 0 writes zeros.
+ * The division by the learner count is left to the caller. */
+int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
+                              const void *const *packets, uint32_t n_learners, float *dense_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- diagnostics ---------------------------------------------------------------------------- */
+
+const char *adacomp_strerror(int code);
+
+/* Where adacomp_compress leaves the g_max vector (one float per bin, layers in table order, bins
+ * in order) inside the workspace: byte offset and number of floats.  For tests of the first loop
+ * of Algorithm 2. */
+int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset,
+                           size_t *n_bins_total);
+
+/* Plain float4 device copy of n floats (dst, src 16-byte aligned): the reference kernel against
+ * which HBM byte counters and the achievable copy bandwidth are calibrated. */
+int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
+
+/* Host-only exhaustive check of the multiply-shift constants the kernels use to turn an element
+ * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
+int adacomp_selftest_binindex(void);
+
+/* Per-kernel timing of adacomp_compress's streaming kernel with HIP events on the caller's
+ * stream.  enable != 0 starts recording (and clears earlier records); adacomp_timing_read
+ * synchronises the recorded events and returns their summed duration and count. */
+int adacomp_timing_enable(int enable);
+int adacomp_timing_read(double *total_ms, uint64_t *n_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,10 @@
+"""libadacomp for MI355X: AdaComp residual-gradient compression (pack / unpack hot path).
+
+The product is the C library ``libadacomp.so`` (sources in ``csrc/``, ABI in ``include/adacomp.h``);
+this package is its ctypes binding.
+"""
+from .binding import (AdacompError, adacomp_compress, adacomp_copy_f32, adacomp_packet_bound,  # noqa: F401
+                      adacomp_packet_fixed_bytes, adacomp_selftest_binindex, adacomp_timing_enable,
+                      adacomp_timing_read, adacomp_unpack_accumulate, adacomp_workspace_bytes,
+                      adacomp_workspace_gmax, adacomp_workspace_init, adacomp_workspace_release,
+                      read_packet_summary)

@@ -1,0 +1,161 @@
+"""ctypes binding of libadacomp's C ABI (include/adacomp.h): argument marshalling only.
+
+Every step of the method runs in the HIP kernels behind these calls.  PyTorch tensors are used as
+device buffers and for the current HIP stream; nothing is computed with torch.  There is no CPU
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadacomp.so")
+
+OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
+    "adacomp_workspace_init", "adacomp_workspace_release", "adacomp_compress",
+    "adacomp_unpack_accumulate", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_copy_f32",
+    "adacomp_selftest_binindex", "adacomp_timing_enable", "adacomp_timing_read",
+]
+
+PACKET_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("status", "<u4"), ("n_layers", "<u4"),
+                          ("total_bytes", "<u8"), ("n_selected", "<u8")])
+PACKET_LAYER = np.dtype([("elem_offset", "<u8"), ("n_elems", "<u8"), ("L_T", "<u4"), ("n_bins", "<u4"),
+                         ("word_bits", "<u4"), ("scale", "<f4"), ("n_selected", "<u8"),
+                         ("counts_offset", "<u8"), ("chunks_offset", "<u8"), ("words_offset", "<u8")])
+
+
+class Layer(ctypes.Structure):
+    _fields_ = [("elem_offset", ctypes.c_uint64), ("n_elems", ctypes.c_uint64),
+                ("L_T", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class AdacompError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libadacomp: {msg} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads libadacomp.so (built beforehand by ``__graft_entry__.build()``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1712_02679_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        LP, u32, sz, vp = ctypes.POINTER(Layer), ctypes.c_uint32, ctypes.c_size_t, ctypes.c_void_p
+        for name in ("adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes"):
+            getattr(L, name).restype = sz
+            getattr(L, name).argtypes = [LP, u32]
+        L.adacomp_workspace_init.argtypes = [LP, u32, vp, sz, vp]
+        L.adacomp_workspace_release.argtypes = [vp]
+        L.adacomp_compress.argtypes = [LP, u32, vp, vp, vp, sz, vp, sz, vp]
+        L.adacomp_unpack_accumulate.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, sz, vp]
+        L.adacomp_strerror.restype = ctypes.c_char_p
+        L.adacomp_strerror.argtypes = [ctypes.c_int]
+        L.adacomp_workspace_gmax.argtypes = [LP, u32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
+        L.adacomp_timing_enable.argtypes = [ctypes.c_int]
+        L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != OK:
+        raise AdacompError(rc, lib().adacomp_strerror(rc).decode())
+
+
+def layer_array(layers):
+    """[(elem_offset, n_elems, L_T)] -> ctypes array of adacomp_layer_t."""
+    arr = (Layer * max(1, len(layers)))()
+    for i, (off, n, lt) in enumerate(layers):
+        arr[i].elem_offset, arr[i].n_elems, arr[i].L_T, arr[i].reserved = int(off), int(n), int(lt), 0
+    return arr
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def adacomp_packet_bound(layers) -> int:
+    return int(lib().adacomp_packet_bound(layer_array(layers), len(layers)))
+
+
+def adacomp_packet_fixed_bytes(layers) -> int:
+    return int(lib().adacomp_packet_fixed_bytes(layer_array(layers), len(layers)))
+
+
+def adacomp_workspace_bytes(layers) -> int:
+    return int(lib().adacomp_workspace_bytes(layer_array(layers), len(layers)))
+
+
+def adacomp_workspace_init(layers, workspace):
+    _check(lib().adacomp_workspace_init(layer_array(layers), len(layers), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_workspace_release(workspace):
+    _check(lib().adacomp_workspace_release(_ptr(workspace)))
+
+
+def adacomp_compress(layers, grad, residue, packet_out, workspace, packet_capacity=None):
+    """grad, residue: float32 CUDA tensors; packet_out, workspace: uint8 CUDA tensors."""
+    cap = packet_out.numel() if packet_capacity is None else int(packet_capacity)
+    _check(lib().adacomp_compress(layer_array(layers), len(layers), _ptr(grad), _ptr(residue),
+                                  _ptr(packet_out), cap, _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_unpack_accumulate(layers, packets, dense_out, workspace):
+    """packets: list of uint8 CUDA tensors (one per learner)."""
+    ptrs = (ctypes.c_void_p * max(1, len(packets)))(*[p.data_ptr() for p in packets])
+    _check(lib().adacomp_unpack_accumulate(layer_array(layers), len(layers), ptrs, len(packets),
+                                           _ptr(dense_out), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_workspace_gmax(layers):
+    off, n = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().adacomp_workspace_gmax(layer_array(layers), len(layers), ctypes.byref(off), ctypes.byref(n)))
+    return off.value, n.value
+
+
+def adacomp_copy_f32(dst, src, n=None):
+    _check(lib().adacomp_copy_f32(_ptr(dst), _ptr(src), dst.numel() if n is None else int(n), _stream()))
+
+
+def adacomp_selftest_binindex() -> int:
+    return int(lib().adacomp_selftest_binindex())
+
+
+def adacomp_timing_enable(on: bool):
+    _check(lib().adacomp_timing_enable(1 if on else 0))
+
+
+def adacomp_timing_read():
+    ms, n = ctypes.c_double(), ctypes.c_uint64()
+    _check(lib().adacomp_timing_read(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
+
+
+def read_packet_summary(packet):
+    """Header and layer records of a packet tensor as numpy records (one small D2H copy)."""
+    head = packet[:32].cpu().numpy().view(PACKET_HEADER)[0]
+    n = int(head["n_layers"])
+    recs = packet[32:32 + 64 * n].cpu().numpy().view(PACKET_LAYER)
+    return head, recs

@@ -1,0 +1,451 @@
+// adacomp_api.hip -- the C ABI of libadacomp: argument checks, the plan (tile tables and
+// workspace layout) and the launch sequences.  No arithmetic of the method lives here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <unordered_map>
+
+#include "adacomp_plan.h"
+
+namespace adacomp {
+
+static uint64_t pad16(uint64_t x) { return (x + 15u) & ~uint64_t(15); }
+static size_t pad256(size_t x) { return (x + 255u) & ~size_t(255); }
+static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b; a = b; b = t; } return a; }
+
+uint32_t bin_magic(uint32_t L_T)
+{
+    // floor(2^32 / L_T) + 1; exact for every index below 2^32 / L_T >= 2^18 (see the self-test).
+    // L_T == 1 would need 2^32 + 1: the kernels special-case it (bin == index).
+    return L_T <= 1 ? 0u : uint32_t((uint64_t(1) << 32) / L_T) + 1u;
+}
+
+int default_register_class()
+{
+    // Elements a thread keeps in registers: 16 * (1 << class).  Class 0 (tiles of 4096 elements)
+    // unless ADACOMP_TILE_CLASS says otherwise; larger bins force a larger class per layer.
+    static int cls = [] {
+        const char *e = std::getenv("ADACOMP_TILE_CLASS");
+        int v = e ? std::atoi(e) : 0;
+        return v < 0 ? 0 : (v > 2 ? 2 : v);
+    }();
+    return cls;
+}
+
+uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    uint64_t h = 1469598103934665603ull;  // FNV-1a over the fields that matter
+    auto mix = [&h](uint64_t v) { for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xFF; h *= 1099511628211ull; } };
+    mix(n_layers);
+    for (uint32_t l = 0; l < n_layers; ++l) { mix(layers[l].elem_offset); mix(layers[l].n_elems); mix(layers[l].L_T); }
+    mix(uint64_t(default_register_class()));
+    return h;
+}
+
+static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    if (!layers || n_layers == 0 || n_layers >= (1u << 24)) return ADACOMP_EINVAL;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        if (layers[l].n_elems == 0 || layers[l].n_elems >= (uint64_t(1) << 31)) return ADACOMP_EINVAL;
+        if (layers[l].L_T == 0 || layers[l].L_T > ADACOMP_LT_MAX) return ADACOMP_EBADLT;
+        if (layers[l].elem_offset % 4 != 0) return ADACOMP_EALIGN;
+        if (layers[l].elem_offset + layers[l].n_elems < layers[l].elem_offset) return ADACOMP_EINVAL;
+    }
+    // overlap check: sort-free O(n^2) is fine for a few hundred layers; use a sorted copy beyond that
+    if (n_layers <= 512) {
+        for (uint32_t l = 0; l < n_layers; ++l)
+            for (uint32_t m = 0; m < l; ++m) {
+                uint64_t a0 = layers[l].elem_offset, a1 = a0 + layers[l].n_elems;
+                uint64_t b0 = layers[m].elem_offset, b1 = b0 + layers[m].n_elems;
+                if (a0 < b1 && b0 < a1) return ADACOMP_EINVAL;
+            }
+    } else {
+        std::vector<std::pair<uint64_t, uint64_t>> iv(n_layers);
+        for (uint32_t l = 0; l < n_layers; ++l) iv[l] = {layers[l].elem_offset, layers[l].elem_offset + layers[l].n_elems};
+        std::sort(iv.begin(), iv.end());
+        for (uint32_t l = 1; l < n_layers; ++l)
+            if (iv[l].first < iv[l - 1].second) return ADACOMP_EINVAL;
+    }
+    return ADACOMP_OK;
+}
+
+int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &p)
+{
+    int rc = validate(layers, n_layers);
+    if (rc != ADACOMP_OK) return rc;
+    p = Plan();
+    p.n_layers = n_layers;
+    p.table_hash = hash_table(layers, n_layers);
+    p.layers.resize(n_layers);
+
+    uint64_t fixed = sizeof(adacomp_packet_header_t) + uint64_t(sizeof(adacomp_packet_layer_t)) * n_layers;
+    uint64_t words_bound = 0;
+    uint64_t n_ctiles = 0, n_utiles = 0, bins_total = 0, chunks_total = 0;
+    const int base_cls = default_register_class();
+
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const uint32_t T = layers[l].L_T;
+        const uint32_t n = uint32_t(layers[l].n_elems);
+        const uint32_t n_bins = (n + T - 1) / T;
+        const uint32_t n_chunks = (n_bins + ADACOMP_CHUNK_BINS - 1) / ADACOMP_CHUNK_BINS;
+        const uint32_t wb = T <= 64 ? 1u : 2u;
+        LayerDev &ld = p.layers[l];
+        ld.elem_offset = layers[l].elem_offset;
+        ld.n_elems = n; ld.L_T = T; ld.n_bins = n_bins; ld.word_bytes = wb; ld.n_chunks = n_chunks; ld.pad0 = 0;
+        ld.counts_offset = fixed;
+        ld.chunks_offset = fixed + pad16(uint64_t(n_bins) * wb);
+        fixed = ld.chunks_offset + pad16(uint64_t(n_chunks) * 4);
+        words_bound += pad16(uint64_t(n) * wb);
+        ld.bin_start = uint32_t(bins_total);
+        ld.chunk_start = uint32_t(chunks_total);
+        bins_total += n_bins;
+        chunks_total += n_chunks;
+        if (bins_total >= (uint64_t(1) << 32)) return ADACOMP_EINVAL;
+        p.elem_span = std::max<uint64_t>(p.elem_span, layers[l].elem_offset + n);
+        p.n_elems_total += n;
+
+        // ---- compress tiles: whole bins, as many as fit the register class --------------------
+        int cls = base_cls;
+        if (T > 4096u && cls < 1) cls = 1;
+        if (T > 8192u) cls = 2;
+        const uint32_t cap = 4096u << cls;
+        uint32_t bpt = cap / T;                       // >= 1
+        if (bpt > kMaxTileBins) bpt = kMaxTileBins;
+        const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
+        if (bpt >= a) bpt -= bpt % a;
+        const uint32_t nt = (n_bins + bpt - 1) / bpt;
+        ld.ctile_start = uint32_t(n_ctiles);
+        ld.n_ctiles = nt;
+        p.has_class[cls] = true;
+        if (tables) {
+            for (uint32_t t = 0; t < nt; ++t) {
+                TileDev td;
+                const uint32_t first_bin = t * bpt;
+                const uint64_t e0 = uint64_t(first_bin) * T;
+                td.elem_base = layers[l].elem_offset + e0;
+                td.n_elems = uint32_t(std::min<uint64_t>(uint64_t(bpt) * T, n - e0));
+                td.L_T = T;
+                td.magic = bin_magic(T);
+                td.n_bins = (td.n_elems + T - 1) / T;
+                td.first_bin = first_bin;
+                td.layer_flags = l | (uint32_t(cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
+                p.ctiles.push_back(td);
+            }
+        }
+        n_ctiles += nt;
+
+        // ---- unpack tiles: a power-of-two number of bins inside one 64-bin chunk, or slices of
+        //      one long bin --------------------------------------------------------------------
+        const uint32_t glog = T <= 64 ? 4u : 6u;      // lanes that share a bin: 16 or 64
+        if (T <= kUnpackTileElems) {
+            uint32_t nb = 1;
+            while (nb * 2 <= ADACOMP_CHUNK_BINS && uint64_t(nb) * 2 * T <= kUnpackTileElems) nb *= 2;
+            const uint32_t nut = (n_bins + nb - 1) / nb;
+            if (tables) {
+                for (uint32_t t = 0; t < nut; ++t) {
+                    UTileDev ut;
+                    const uint32_t first_bin = t * nb;
+                    const uint64_t e0 = uint64_t(first_bin) * T;
+                    ut.elem_base = layers[l].elem_offset + e0;
+                    ut.n_elems = uint32_t(std::min<uint64_t>(uint64_t(nb) * T, n - e0));
+                    ut.L_T = T;
+                    ut.n_bins = (ut.n_elems + T - 1) / T;
+                    ut.first_bin = first_bin;
+                    ut.idx_lo = 0;
+                    ut.layer_flags = l | (glog << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
+                    p.utiles.push_back(ut);
+                }
+            }
+            n_utiles += nut;
+        } else {
+            for (uint32_t b = 0; b < n_bins; ++b) {
+                const uint64_t b0 = uint64_t(b) * T;
+                const uint32_t blen = uint32_t(std::min<uint64_t>(T, n - b0));
+                for (uint32_t lo = 0; lo < blen; lo += kUnpackTileElems) {
+                    if (tables) {
+                        UTileDev ut;
+                        ut.elem_base = layers[l].elem_offset + b0 + lo;
+                        ut.n_elems = std::min(kUnpackTileElems, blen - lo);
+                        ut.L_T = T;
+                        ut.n_bins = 1;
+                        ut.first_bin = b;
+                        ut.idx_lo = lo;
+                        ut.layer_flags = l | (glog << 24) | (((b0 + lo) % 4 == 0) ? 0x80000000u : 0u);
+                        p.utiles.push_back(ut);
+                    }
+                    ++n_utiles;
+                }
+            }
+        }
+        if (n_ctiles >= (1u << 31) || n_utiles >= (1u << 31)) return ADACOMP_EINVAL;
+    }
+    p.n_ctiles = uint32_t(n_ctiles);
+    p.n_utiles = uint32_t(n_utiles);
+    p.n_bins_total = uint32_t(bins_total);
+    p.n_chunks_total = uint32_t(chunks_total);
+    p.fixed_bytes = fixed;
+    p.bound_bytes = fixed + words_bound;
+
+    WorkspaceLayout &w = p.ws;
+    size_t off = 256;  // first 256 bytes: reserved
+    w.layers = off;      off = pad256(off + sizeof(LayerDev) * size_t(n_layers));
+    w.ctiles = off;      off = pad256(off + sizeof(TileDev) * size_t(p.n_ctiles));
+    w.utiles = off;      off = pad256(off + sizeof(UTileDev) * size_t(p.n_utiles));
+    w.tile_count = off;  off = pad256(off + 4 * size_t(p.n_ctiles));
+    w.tile_base = off;   off = pad256(off + 4 * size_t(p.n_ctiles));
+    w.tile_sum = off;    off = pad256(off + 8 * size_t(p.n_ctiles));
+    w.layer_nsel = off;  off = pad256(off + 4 * size_t(n_layers));
+    w.layer_scale = off; off = pad256(off + 4 * size_t(n_layers));
+    w.gmax = off;        off = pad256(off + 4 * size_t(p.n_bins_total));
+    w.chunk_rel = off;   off = pad256(off + 4 * size_t(p.n_chunks_total));
+    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span));
+    w.total = off;
+    return ADACOMP_OK;
+}
+
+// Workspaces that adacomp_workspace_init has filled, by address.
+struct Registered { Plan plan; };
+static std::mutex g_mu;
+static std::unordered_map<const void *, Registered> g_ws;
+
+static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace,
+                     size_t workspace_bytes, Plan &out)
+{
+    if (!layers || n_layers == 0 || !workspace) return ADACOMP_EINVAL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_ws.find(workspace);
+    if (it == g_ws.end()) return ADACOMP_EWORKSPACE;
+    const Plan &p = it->second.plan;
+    if (p.n_layers != n_layers || p.table_hash != hash_table(layers, n_layers)) return ADACOMP_EWORKSPACE;
+    if (workspace_bytes < p.ws.total) return ADACOMP_EWORKSPACE;
+    // copy the scalars only; the tables already live on the device
+    out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles;
+    out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
+    out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
+    out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
+    for (int c = 0; c < 3; ++c) out.has_class[c] = p.has_class[c];
+    out.table_hash = p.table_hash; out.ws = p.ws;
+    return ADACOMP_OK;
+}
+
+// ---- optional event timing of the streaming kernel ---------------------------------------------
+struct Timing {
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+    size_t used = 0;
+};
+static Timing g_timing;
+
+}  // namespace adacomp
+
+using namespace adacomp;
+
+extern "C" {
+
+size_t adacomp_packet_bound(const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    Plan p;
+    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? size_t(p.bound_bytes) : 0;
+}
+
+size_t adacomp_packet_fixed_bytes(const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    Plan p;
+    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? size_t(p.fixed_bytes) : 0;
+}
+
+size_t adacomp_workspace_bytes(const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    Plan p;
+    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? p.ws.total : 0;
+}
+
+int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset, size_t *n_bins_total)
+{
+    if (!byte_offset || !n_bins_total) return ADACOMP_EINVAL;
+    Plan p;
+    int rc = build_plan(layers, n_layers, false, p);
+    if (rc != ADACOMP_OK) return rc;
+    *byte_offset = p.ws.gmax;
+    *n_bins_total = p.n_bins_total;
+    return ADACOMP_OK;
+}
+
+int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    if (!workspace) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return ADACOMP_EALIGN;
+    Registered reg;
+    int rc = build_plan(layers, n_layers, true, reg.plan);
+    if (rc != ADACOMP_OK) return rc;
+    Plan &p = reg.plan;
+    if (workspace_bytes < p.ws.total) return ADACOMP_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (hipStreamSynchronize(s) != hipSuccess) return ADACOMP_EHIP;
+    char *ws = static_cast<char *>(workspace);
+    if (hipMemcpy(ws + p.ws.layers, p.layers.data(), sizeof(LayerDev) * p.layers.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(ws + p.ws.ctiles, p.ctiles.data(), sizeof(TileDev) * p.ctiles.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(ws + p.ws.utiles, p.utiles.data(), sizeof(UTileDev) * p.utiles.size(), hipMemcpyHostToDevice) != hipSuccess)
+        return ADACOMP_EHIP;
+    // the host copies of the tile tables are no longer needed
+    p.ctiles.clear(); p.ctiles.shrink_to_fit();
+    p.utiles.clear(); p.utiles.shrink_to_fit();
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_ws[workspace] = std::move(reg);
+    return ADACOMP_OK;
+}
+
+int adacomp_workspace_release(void *workspace)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    return g_ws.erase(workspace) ? ADACOMP_OK : ADACOMP_EINVAL;
+}
+
+int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
+                     float *residue, void *packet_out, size_t packet_capacity, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    if (!grad || !residue || !packet_out || grad == residue) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(grad) % 16 || reinterpret_cast<uintptr_t>(residue) % 16 ||
+        reinterpret_cast<uintptr_t>(packet_out) % 16)
+        return ADACOMP_EALIGN;
+    Plan p;
+    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, p);
+    if (rc != ADACOMP_OK) return rc;
+    if (packet_capacity < p.fixed_bytes) return ADACOMP_ENOSPC;
+
+    char *ws = static_cast<char *>(workspace);
+    CompressArgs a;
+    a.tiles = reinterpret_cast<const TileDev *>(ws + p.ws.ctiles);
+    a.layers = reinterpret_cast<const LayerDev *>(ws + p.ws.layers);
+    a.grad = grad;
+    a.residue = residue;
+    a.packet = static_cast<uint8_t *>(packet_out);
+    a.capacity = packet_capacity;
+    a.tile_count = reinterpret_cast<uint32_t *>(ws + p.ws.tile_count);
+    a.tile_base = reinterpret_cast<uint32_t *>(ws + p.ws.tile_base);
+    a.tile_sum = reinterpret_cast<double *>(ws + p.ws.tile_sum);
+    a.layer_nsel = reinterpret_cast<uint32_t *>(ws + p.ws.layer_nsel);
+    a.layer_scale = reinterpret_cast<float *>(ws + p.ws.layer_scale);
+    a.gmax = reinterpret_cast<float *>(ws + p.ws.gmax);
+    a.chunk_rel = reinterpret_cast<uint32_t *>(ws + p.ws.chunk_rel);
+    a.stage = reinterpret_cast<uint16_t *>(ws + p.ws.stage);
+    a.n_tiles = p.n_ctiles;
+    a.n_layers = p.n_layers;
+    a.fixed_bytes = p.fixed_bytes;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
+    if (g_timing.on) {
+        if (g_timing.used == g_timing.pool.size()) {
+            hipEvent_t e0, e1;
+            if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
+            g_timing.pool.emplace_back(e0, e1);
+        }
+        ev = &g_timing.pool[g_timing.used++];
+        if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
+    }
+    for (int c = 0; c < 3; ++c)
+        if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
+    if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
+    if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
+    return launch_place(a, hip_stream);
+}
+
+int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
+                              const void *const *packets, uint32_t n_learners, float *dense_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!dense_out || (n_learners > 0 && !packets)) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dense_out) % 16) return ADACOMP_EALIGN;
+    for (uint32_t k = 0; k < n_learners; ++k) {
+        if (!packets[k]) return ADACOMP_EINVAL;
+        if (reinterpret_cast<uintptr_t>(packets[k]) % 16) return ADACOMP_EALIGN;
+    }
+    Plan p;
+    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, p);
+    if (rc != ADACOMP_OK) return rc;
+
+    char *ws = static_cast<char *>(workspace);
+    UnpackArgs a;
+    a.tiles = reinterpret_cast<const UTileDev *>(ws + p.ws.utiles);
+    a.layers = reinterpret_cast<const LayerDev *>(ws + p.ws.layers);
+    a.dense = dense_out;
+    a.n_tiles = p.n_utiles;
+    a.n_layers = p.n_layers;
+    uint32_t done = 0;
+    do {  // 64 learners per launch; later launches add onto the stored partial sum, same order
+        const uint32_t now = std::min(n_learners - done, kMaxPacketArgs);
+        a.n_learners = now;
+        a.accumulate = done > 0;
+        for (uint32_t k = 0; k < kMaxPacketArgs; ++k)
+            a.packets[k] = k < now ? static_cast<const uint8_t *>(packets[done + k]) : nullptr;
+        if ((rc = launch_unpack(a, hip_stream)) != ADACOMP_OK) return rc;
+        done += now;
+    } while (done < n_learners);
+    return ADACOMP_OK;
+}
+
+const char *adacomp_strerror(int code)
+{
+    switch (code) {
+    case ADACOMP_OK: return "ok";
+    case ADACOMP_EINVAL: return "invalid argument (null pointer, empty or overlapping layer, aliasing buffers)";
+    case ADACOMP_EBADLT: return "L_T must be in 1..16384";
+    case ADACOMP_EALIGN: return "elem_offset must be a multiple of 4 and buffers 16-byte aligned (workspace 256)";
+    case ADACOMP_ENOSPC: return "packet capacity below the fixed part of the packet";
+    case ADACOMP_EHIP: return "HIP runtime error (no device or failed launch)";
+    case ADACOMP_EWORKSPACE: return "workspace too small or not initialised for this layer table";
+    default: return "unknown adacomp error";
+    }
+}
+
+int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream)
+{
+    if (!dst || !src) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16) return ADACOMP_EALIGN;
+    return n == 0 ? ADACOMP_OK : launch_copy(dst, src, n, hip_stream);
+}
+
+int adacomp_selftest_binindex(void)
+{
+    for (uint32_t T = 2; T <= ADACOMP_LT_MAX; ++T) {
+        const uint32_t m = bin_magic(T);
+        uint32_t q = 0, r = 0;  // running e / T, e % T
+        for (uint32_t e = 0; e < 16384u; ++e) {
+            if (uint32_t((uint64_t(e) * m) >> 32) != q) return -1;
+            if (++r == T) { r = 0; ++q; }
+        }
+    }
+    return 0;
+}
+
+int adacomp_timing_enable(int enable)
+{
+    g_timing.on = enable != 0;
+    g_timing.used = 0;
+    return ADACOMP_OK;
+}
+
+int adacomp_timing_read(double *total_ms, uint64_t *n_launches)
+{
+    if (!total_ms || !n_launches) return ADACOMP_EINVAL;
+    double sum = 0.0;
+    for (size_t i = 0; i < g_timing.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_timing.pool[i].second) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_timing.pool[i].first, g_timing.pool[i].second) != hipSuccess)
+            return ADACOMP_EHIP;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *n_launches = g_timing.used;
+    g_timing.used = 0;
+    return ADACOMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,536 @@
+// adacomp_kernels.hip -- the hot path of libadacomp as hand-written HIP for gfx950 (CDNA4,
+// wave64).  Everything here is bound by HBM traffic, not arithmetic: there is no dense
+// contraction, hence no MFMA.  All floating-point work is single additions / subtractions in
+// float32 (no multiplies, nothing to contract) plus one float64 sum and divide per layer.
+//
+// adacomp_compress runs three launches:
+//   k_fused  (streaming, dominant)  one pass over dW and the residue: G = R + dW, H = G + dW, the
+//            per-bin maximum of |G|, the selection compare, and R <- G, all while the tile sits
+//            in registers (Algorithm 2 of the AdaComp paper, both loops; selection is local to a
+//            bin, so nothing outside the tile is needed).  Selected elements leave as 16-bit
+//            (tile-local index, sign) entries in a staging area, counts per bin go straight into
+//            the packet, g_max and its per-tile float64 sum go to scratch.
+//   k_scan   one workgroup per layer: the layer scale = average of the g_max vector (section
+//            "Pseudo code") and the exclusive scan of per-tile word counts.
+//   k_place  one wave per tile: moves the staged entries to their final place in the packet as
+//            (index-in-bin, ternary code) words and applies the only step that needs the
+//            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
+//            about 1-10 % of the elements); one extra workgroup writes header and records.
+// adacomp_unpack_accumulate is one launch, k_unpack: a workgroup owns a tile of the dense output
+// in LDS, a lane group owns each bin and adds the learners' +-scale in learner order, then the
+// tile is written out once with coalesced float4 stores.
+#include <hip/hip_runtime.h>
+
+#include "adacomp_plan.h"
+
+namespace adacomp {
+
+// ---- small device helpers --------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bin_of(uint32_t e, uint32_t L_T, uint32_t magic)
+{
+    return L_T == 1u ? e : __umulhi(e, magic);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+{
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+{
+#pragma unroll
+    for (uint32_t d = 32; d > 0; d >>= 1) {
+        uint32_t lo = __shfl_xor(uint32_t(v), d, 64), hi = __shfl_xor(uint32_t(v >> 32), d, 64);
+        v += (uint64_t(hi) << 32) | lo;
+    }
+    return v;
+}
+
+// Sum of one double per lane, fixed pairing (lane i with lane i + d): deterministic.
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
+    return v;  // valid in lane 0
+}
+
+// ==============================================================================================
+// k_fused: Algorithm 2, both loops, on a tile of whole bins held in registers.
+// Thread t owns float4 slots t, t + 256, ...: element e = 4 * (j * 256 + t) + c of the tile.
+// ==============================================================================================
+template <int J>
+__global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
+{
+    const uint32_t tile = blockIdx.x;
+    if (tile >= a.n_tiles) return;
+    const TileDev td = a.tiles[tile];
+    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
+
+    __shared__ uint32_t s_gmax[kMaxTileBins];  // bit pattern of max |G|: for non-negative floats the
+    __shared__ uint32_t s_cnt[kMaxTileBins];   // unsigned integer order is the float order
+    __shared__ uint32_t s_wtot[64];
+    __shared__ double s_red[4];
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+    const uint32_t n = td.n_elems, T = td.L_T, M = td.magic, nb = td.n_bins;
+    const bool vec = td.aligned();
+
+    for (uint32_t i = tid; i < nb; i += kWG) { s_gmax[i] = 0u; s_cnt[i] = 0u; }
+
+    const float *__restrict__ gr = a.grad + td.elem_base;
+    float *__restrict__ rs = a.residue + td.elem_base;
+
+    // ---- G <- residue + dW ; H <- G + dW ; residue <- G (the "no transmission" value) ----------
+    float r[J][4], w[J][4];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        if (vec && e0 + 4u <= n) {
+            const float4 rv = *reinterpret_cast<const float4 *>(rs + e0);
+            const float4 wv = *reinterpret_cast<const float4 *>(gr + e0);
+            r[j][0] = rv.x; r[j][1] = rv.y; r[j][2] = rv.z; r[j][3] = rv.w;
+            w[j][0] = wv.x; w[j][1] = wv.y; w[j][2] = wv.z; w[j][3] = wv.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool ok = e0 + uint32_t(c) < n;
+                r[j][c] = ok ? rs[e0 + c] : 0.f;
+                w[j][c] = ok ? gr[e0 + c] : 0.f;
+            }
+        }
+    }
+    uint32_t gb[J][4];  // bits of G (sign included)
+    uint32_t mb[J][4];  // bits of max(|G|, |H|): what is compared with g_max
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        float G[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            G[c] = r[j][c] + w[j][c];
+            const float H = G[c] + w[j][c];
+            gb[j][c] = __float_as_uint(G[c]);
+            const uint32_t ag = gb[j][c] & 0x7FFFFFFFu, ah = __float_as_uint(H) & 0x7FFFFFFFu;
+            mb[j][c] = ag > ah ? ag : ah;
+        }
+        if (vec && e0 + 4u <= n) {
+            *reinterpret_cast<float4 *>(rs + e0) = make_float4(G[0], G[1], G[2], G[3]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (e0 + uint32_t(c) < n) rs[e0 + c] = G[c];
+        }
+    }
+
+    __syncthreads();  // LDS arrays are zeroed
+
+    // ---- first loop of Algorithm 2: g_max(i) per bin -------------------------------------------
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        if (e0 < n) {
+            const uint32_t e3 = e0 + 3u < n ? e0 + 3u : n - 1u;
+            const uint32_t b0 = bin_of(e0, T, M), b3 = bin_of(e3, T, M);
+            if (b0 == b3) {
+                uint32_t m = gb[j][0] & 0x7FFFFFFFu;   // elements past n hold G = 0: they never raise a maximum
+#pragma unroll
+                for (int c = 1; c < 4; ++c) { const uint32_t v = gb[j][c] & 0x7FFFFFFFu; m = v > m ? v : m; }
+                atomicMax(&s_gmax[b0], m);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (e0 + uint32_t(c) < n) atomicMax(&s_gmax[bin_of(e0 + c, T, M)], gb[j][c] & 0x7FFFFFFFu);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- second loop: the local-max compare.  Sent iff G != 0 and max(|H|, |G|) >= g_max -------
+    uint32_t before[J];  // sent elements of this wave's slot row that precede this lane
+    uint32_t flags[J];   // bit c: element c of the slot is sent
+    uint32_t wtot[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        uint32_t f = 0u;
+        if (e0 < n) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t e = e0 + uint32_t(c);
+                if (e < n) {
+                    const uint32_t gm = s_gmax[bin_of(e, T, M)];
+                    const bool sent = ((gb[j][c] & 0x7FFFFFFFu) != 0u) && (mb[j][c] >= gm);
+                    f |= sent ? (1u << c) : 0u;
+                }
+            }
+        }
+        flags[j] = f;
+        uint32_t acc = 0u, tot = 0u;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint64_t m = __ballot((f >> c) & 1u);
+            acc = __builtin_amdgcn_mbcnt_hi(uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), acc));
+            tot += uint32_t(__popcll(m));
+        }
+        before[j] = acc;
+        wtot[j] = tot;
+        if (lane == 0) s_wtot[j * 4 + wave] = tot;
+    }
+    __syncthreads();
+
+    // element order inside the tile is (j, wave, lane, c): exclusive prefix over the 4 J rows
+    const uint32_t row_incl = wave_incl_scan(lane < uint32_t(4 * J) ? s_wtot[lane] : 0u, lane);
+    const uint32_t tile_total = __shfl(row_incl, 4 * J - 1, 64);
+
+    // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
+    uint16_t *__restrict__ stage = a.stage + td.elem_base;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        uint32_t pos = __shfl(row_incl, j * 4 + int(wave), 64) - wtot[j] + before[j];
+        const uint32_t f = flags[j];
+        if (f) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if ((f >> c) & 1u) {
+                    const uint32_t e = e0 + uint32_t(c);
+                    const uint32_t code = (gb[j][c] >> 31) ? 3u : 1u;  // ternary value: -scale / +scale
+                    stage[pos] = uint16_t((e << 2) | code);
+                    ++pos;
+                    atomicAdd(&s_cnt[bin_of(e, T, M)], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- tile outputs: counts (into the packet), g_max, sum of g_max, chunk prefixes, total ----
+    const LayerDev ld = a.layers[td.layer()];
+    if (ld.word_bytes == 1u) {
+        uint8_t *cp = a.packet + ld.counts_offset + td.first_bin;
+        for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint8_t(s_cnt[i]);
+    } else {
+        uint16_t *cp = reinterpret_cast<uint16_t *>(a.packet + ld.counts_offset) + td.first_bin;
+        for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint16_t(s_cnt[i]);
+    }
+    double part = 0.0;
+    float *gm_out = a.gmax + ld.bin_start + td.first_bin;
+    for (uint32_t i = tid; i < nb; i += kWG) {
+        const float g = __uint_as_float(s_gmax[i]);
+        gm_out[i] = g;
+        part += double(g);
+    }
+    part = wave_sum_f64(part);
+    if (lane == 0) s_red[wave] = part;
+    // running word count at every 64th bin of the layer that falls inside this tile
+    const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
+    for (uint32_t t = t0 + 64u * wave; t < nb; t += 64u * 4u) {
+        uint32_t sum = 0u;
+        for (uint32_t i = lane; i < t; i += 64u) sum += s_cnt[i];
+        sum = wave_sum(sum);
+        if (lane == 0) a.chunk_rel[ld.chunk_start + ((td.first_bin + t) >> 6)] = sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        a.tile_sum[tile] = ((s_red[0] + s_red[1]) + s_red[2]) + s_red[3];
+        a.tile_count[tile] = tile_total;
+    }
+}
+
+// ==============================================================================================
+// k_scan: per layer, scale = (sum of g_max) / n_bins in float64 rounded once to float32, and the
+// exclusive scan of the tiles' word counts.
+// ==============================================================================================
+__global__ __launch_bounds__(kWG) void k_scan(const CompressArgs a)
+{
+    const uint32_t l = blockIdx.x;
+    if (l >= a.n_layers) return;
+    const LayerDev ld = a.layers[l];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+    const uint32_t nt = ld.n_ctiles, ts = ld.ctile_start;
+    const uint32_t per = (nt + kWG - 1) / kWG;
+    const uint32_t lo = tid * per < nt ? tid * per : nt;
+    const uint32_t hi = lo + per < nt ? lo + per : nt;
+
+    __shared__ uint32_t s_wsum[4];
+    __shared__ double s_dsum[4];
+
+    uint32_t csum = 0u;
+    double dsum = 0.0;
+    for (uint32_t i = lo; i < hi; ++i) { csum += a.tile_count[ts + i]; dsum += a.tile_sum[ts + i]; }
+
+    const uint32_t incl = wave_incl_scan(csum, lane);
+    dsum = wave_sum_f64(dsum);
+    if (lane == 63) s_wsum[wave] = incl;
+    if (lane == 0) s_dsum[wave] = dsum;
+    __syncthreads();
+    uint32_t wave_base = 0u;
+    for (uint32_t wv = 0; wv < wave; ++wv) wave_base += s_wsum[wv];
+    uint32_t run = wave_base + incl - csum;
+    for (uint32_t i = lo; i < hi; ++i) { a.tile_base[ts + i] = run; run += a.tile_count[ts + i]; }
+    if (tid == 0) {
+        const double total = ((s_dsum[0] + s_dsum[1]) + s_dsum[2]) + s_dsum[3];
+        a.layer_scale[l] = float(total / double(ld.n_bins));
+        a.layer_nsel[l] = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+    }
+}
+
+// ==============================================================================================
+// k_place: staged entries -> final words; residue <- G - Gq at the sent elements; chunk offsets;
+// header, records and padding (last workgroup).
+// ==============================================================================================
+__device__ __forceinline__ uint64_t pad16_dev(uint64_t x) { return (x + 15u) & ~uint64_t(15); }
+
+__global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+
+    if (blockIdx.x == gridDim.x - 1) {
+        // ---- header, layer records, zero padding ------------------------------------------------
+        __shared__ uint64_t s_total, s_nsel;
+        if (tid == 0) { s_total = 0; s_nsel = 0; }
+        __syncthreads();
+        for (uint32_t l = tid; l < a.n_layers; l += kWG) {
+            const LayerDev ld = a.layers[l];
+            uint64_t woff = a.fixed_bytes;
+            for (uint32_t m = 0; m < l; ++m) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
+            const uint64_t nsel = a.layer_nsel[l];
+            adacomp_packet_layer_t rec;
+            rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
+            rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
+            rec.scale = a.layer_scale[l];
+            rec.n_selected = nsel;
+            rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
+            reinterpret_cast<adacomp_packet_layer_t *>(a.packet + sizeof(adacomp_packet_header_t))[l] = rec;
+            for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) a.packet[b] = 0;
+            const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
+            for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) a.packet[b] = 0;
+            const uint64_t words_end = woff + nsel * ld.word_bytes;
+            for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
+                if (b < a.capacity) a.packet[b] = 0;
+            if (l == a.n_layers - 1) s_total = pad16_dev(words_end);
+            atomicAdd(reinterpret_cast<unsigned long long *>(&s_nsel), (unsigned long long)nsel);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            adacomp_packet_header_t h;
+            h.magic = ADACOMP_PACKET_MAGIC; h.version = ADACOMP_PACKET_VERSION;
+            h.status = s_total > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
+            h.n_layers = a.n_layers; h.total_bytes = s_total; h.n_selected = s_nsel;
+            *reinterpret_cast<adacomp_packet_header_t *>(a.packet) = h;
+        }
+        return;
+    }
+
+    const uint32_t tile = blockIdx.x * 4u + wave;
+    if (tile >= a.n_tiles) return;
+    const TileDev td = a.tiles[tile];
+    const uint32_t l = td.layer();
+    const LayerDev ld = a.layers[l];
+
+    // first word of this layer = end of the fixed part + the (padded) word sections before it
+    uint64_t woff = 0;
+    for (uint32_t m = lane; m < l; m += 64u) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
+    woff = wave_sum64(woff) + a.fixed_bytes;
+
+    const uint32_t cnt = a.tile_count[tile], base = a.tile_base[tile];
+    const float scale = a.layer_scale[l];
+    const uint16_t *__restrict__ stage = a.stage + td.elem_base;
+    float *__restrict__ rs = a.residue + td.elem_base;
+    const uint32_t T = td.L_T, M = td.magic;
+
+    for (uint32_t p = lane; p < cnt; p += 64u) {
+        const uint32_t s = stage[p];
+        const uint32_t e = s >> 2, code = s & 3u;
+        const uint32_t b = bin_of(e, T, M);
+        const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
+        const uint64_t at = woff + uint64_t(base + p) * ld.word_bytes;
+        if (at + ld.word_bytes <= a.capacity) {
+            if (ld.word_bytes == 1u) a.packet[at] = uint8_t(word);
+            else *reinterpret_cast<uint16_t *>(a.packet + at) = uint16_t(word);
+        }
+        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left there
+        const float g = rs[e];
+        rs[e] = code == 1u ? g - scale : g + scale;
+    }
+
+    // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
+    const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
+    for (uint32_t t = t0 + 64u * lane; t < td.n_bins; t += 64u * 64u) {
+        const uint32_t c = (td.first_bin + t) >> 6;
+        reinterpret_cast<uint32_t *>(a.packet + ld.chunks_offset)[c] = base + a.chunk_rel[ld.chunk_start + c];
+    }
+}
+
+// ==============================================================================================
+// k_unpack: dense_out <- sum over learners, in learner order, of the decoded packets.
+// ==============================================================================================
+__global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
+{
+    const uint32_t tile = blockIdx.x;
+    if (tile >= a.n_tiles) return;
+    const UTileDev ut = a.tiles[tile];
+    const LayerDev ld = a.layers[ut.layer()];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+    const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
+    const bool vec = ut.aligned();
+    float *__restrict__ out = a.dense + ut.elem_base;
+
+    __shared__ float s_acc[kUnpackTileElems];
+    __shared__ uint32_t s_start[kLearnerGroup][64];  // first word of (learner, bin) inside the layer's words
+    __shared__ uint32_t s_cnt[kLearnerGroup][64];
+    __shared__ float s_scale[kLearnerGroup];
+    __shared__ uint64_t s_words[kLearnerGroup];      // address of the layer's first word
+
+    // ---- tile accumulators: zero, or the partial sum of an earlier launch ----------------------
+    for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.accumulate) {
+            if (vec && i + 4u <= n) v = *reinterpret_cast<const float4 *>(out + i);
+            else {
+                v.x = out[i];
+                v.y = i + 1u < n ? out[i + 1] : 0.f;
+                v.z = i + 2u < n ? out[i + 2] : 0.f;
+                v.w = i + 3u < n ? out[i + 3] : 0.f;
+            }
+        }
+        *reinterpret_cast<float4 *>(&s_acc[i]) = v;  // s_acc has room for the rounded-up tail
+    }
+
+    const uint32_t chunk = ut.first_bin >> 6;
+    const uint32_t chunk_bin0 = chunk << 6;
+    const uint32_t glog = ut.group_log2(), gsz = 1u << glog;
+
+    for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
+        const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
+        __syncthreads();  // accumulators initialised / previous group finished with the tables
+
+        // ---- per learner: where each bin's words start (one wave per learner) ------------------
+        for (uint32_t kk = wave; kk < nk; kk += 4u) {
+            const uint8_t *pk = a.packets[k0 + kk];
+            const adacomp_packet_header_t *h = reinterpret_cast<const adacomp_packet_header_t *>(pk);
+            const bool ok = h->magic == ADACOMP_PACKET_MAGIC && h->version == ADACOMP_PACKET_VERSION &&
+                            h->status == ADACOMP_STATUS_COMPLETE && h->n_layers == a.n_layers;
+            const adacomp_packet_layer_t *rec =
+                reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
+            const uint32_t b = chunk_bin0 + lane;
+            const bool mine = ok && b < ut.first_bin + nb;
+            uint32_t c = 0u;
+            if (mine) c = ld.word_bytes == 1u ? uint32_t(pk[ld.counts_offset + b])
+                                              : uint32_t(reinterpret_cast<const uint16_t *>(pk + ld.counts_offset)[b]);
+            const uint32_t incl = wave_incl_scan(c, lane);
+            const uint32_t coff = ok ? reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk] : 0u;
+            if (b >= ut.first_bin && b < ut.first_bin + nb) {
+                s_start[kk][b - ut.first_bin] = coff + incl - c;
+                s_cnt[kk][b - ut.first_bin] = c;
+            }
+            if (lane == 0) {
+                s_scale[kk] = ok ? rec->scale : 0.f;
+                s_words[kk] = ok ? uint64_t(reinterpret_cast<uintptr_t>(pk + rec->words_offset)) : 0ull;
+            }
+        }
+        __syncthreads();
+
+        // ---- a lane group owns a bin and adds its learners' values in learner order.  The adds to
+        //      one LDS address all come from one wave in program order, so the order is fixed. ----
+        for (uint32_t s = tid; s < (nb << glog); s += kWG) {
+            const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
+            const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
+            float *acc = s_acc + lb * T;
+            for (uint32_t kk = 0; kk < nk; ++kk) {
+                const uint32_t c = s_cnt[kk][lb], st = s_start[kk][lb];
+                const float sc = s_scale[kk];
+                const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
+                for (uint32_t jw = sub; jw < c; jw += gsz) {
+                    const uint32_t word = ld.word_bytes == 1u ? uint32_t(wp[st + jw])
+                                                              : uint32_t(reinterpret_cast<const uint16_t *>(wp)[st + jw]);
+                    const uint32_t idx = (word >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
+                    const uint32_t code = word & 3u;
+                    if (idx < span && (code & 1u)) acc[idx] += code == 1u ? sc : -sc;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
+        const float4 v = *reinterpret_cast<const float4 *>(&s_acc[i]);
+        if (vec && i + 4u <= n) *reinterpret_cast<float4 *>(out + i) = v;
+        else {
+            out[i] = v.x;
+            if (i + 1u < n) out[i + 1] = v.y;
+            if (i + 2u < n) out[i + 2] = v.z;
+            if (i + 3u < n) out[i + 3] = v.w;
+        }
+    }
+}
+
+// ==============================================================================================
+// k_copy: plain float4 copy, the calibration kernel for byte counters and copy bandwidth.
+// ==============================================================================================
+__global__ __launch_bounds__(kWG) void k_copy(float *__restrict__ dst, const float *__restrict__ src, size_t n)
+{
+    const size_t n4 = n / 4;
+    const size_t stride = size_t(gridDim.x) * kWG;
+    for (size_t i = size_t(blockIdx.x) * kWG + threadIdx.x; i < n4; i += stride)
+        reinterpret_cast<float4 *>(dst)[i] = reinterpret_cast<const float4 *>(src)[i];
+    if (blockIdx.x == 0 && threadIdx.x < n % 4) dst[n4 * 4 + threadIdx.x] = src[n4 * 4 + threadIdx.x];
+}
+
+// ---- launchers ---------------------------------------------------------------------------------
+static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK : ADACOMP_EHIP; }
+
+int launch_fused(const CompressArgs &a, int jcode, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    else hipLaunchKernelGGL(k_fused<16>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    return check_launch();
+}
+
+int launch_scan(const CompressArgs &a, void *stream)
+{
+    hipLaunchKernelGGL(k_scan, dim3(a.n_layers), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    return check_launch();
+}
+
+int launch_place(const CompressArgs &a, void *stream)
+{
+    hipLaunchKernelGGL(k_place, dim3((a.n_tiles + 3u) / 4u + 1u), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    return check_launch();
+}
+
+int launch_unpack(const UnpackArgs &a, void *stream)
+{
+    hipLaunchKernelGGL(k_unpack, dim3(a.n_tiles), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    return check_launch();
+}
+
+int launch_copy(float *dst, const float *src, size_t n, void *stream)
+{
+    const size_t n4 = n / 4;
+    size_t blocks = (n4 + kWG - 1) / kWG;
+    if (blocks > 256u * 32u) blocks = 256u * 32u;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(k_copy, dim3(uint32_t(blocks)), dim3(kWG), 0, static_cast<hipStream_t>(stream), dst, src, n);
+    return check_launch();
+}
+
+}  // namespace adacomp

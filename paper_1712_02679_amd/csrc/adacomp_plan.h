@@ -1,0 +1,127 @@
+// adacomp_plan.h -- host-side plan (tile tables, workspace layout) and the structures the
+// kernels read from device memory.  Internal to libadacomp.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "adacomp.h"
+
+namespace adacomp {
+
+constexpr uint32_t kWG = 256;            // threads per workgroup in every kernel (4 wave64)
+constexpr uint32_t kMaxTileBins = 1024;  // bins per compress tile (LDS arrays)
+constexpr uint32_t kUnpackTileElems = 4096;  // elements per unpack tile (16 KB of LDS accumulators)
+constexpr uint32_t kLearnerGroup = 16;   // learners whose bin tables sit in LDS together in unpack
+constexpr uint32_t kMaxPacketArgs = 64;  // packet pointers passed by value per unpack launch
+
+// A layer as the kernels see it (64 bytes).
+struct LayerDev {
+    uint64_t elem_offset;
+    uint64_t counts_offset;  // byte offsets inside a packet; fixed by the layer table alone
+    uint64_t chunks_offset;
+    uint32_t n_elems, L_T, n_bins, word_bytes;
+    uint32_t ctile_start, n_ctiles;  // this layer's compress tiles in the tile table
+    uint32_t bin_start, chunk_start; // first global bin / chunk index (g_max, chunk scratch arrays)
+    uint32_t n_chunks, pad0;
+};
+static_assert(sizeof(LayerDev) == 64, "LayerDev layout");
+
+// One workgroup's share of adacomp_compress: whole bins of one layer (32 bytes).
+struct TileDev {
+    uint64_t elem_base;   // first element in grad / residue (layer offset included)
+    uint32_t n_elems;     // elements in the tile, <= 1024 * J
+    uint32_t L_T;
+    uint32_t magic;       // floor(2^32 / L_T) + 1: bin = umulhi(e, magic) for e < 16384 (L_T > 1)
+    uint32_t n_bins;      // bins in the tile, <= kMaxTileBins
+    uint32_t first_bin;   // index of the tile's first bin inside the layer
+    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16), bit 31 aligned
+    __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
+    __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 3u; }
+    __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
+};
+static_assert(sizeof(TileDev) == 32, "TileDev layout");
+
+// One workgroup's share of adacomp_unpack_accumulate: up to 64 whole bins inside one 64-bin
+// chunk, or a slice [idx_lo, idx_lo + n_elems) of a single bin longer than the tile (32 bytes).
+struct UTileDev {
+    uint64_t elem_base;
+    uint32_t n_elems;
+    uint32_t L_T;
+    uint32_t n_bins;
+    uint32_t first_bin;
+    uint32_t idx_lo;
+    uint32_t layer_flags; // bits 0..23 layer, 24..27 log2(lanes per bin), bit 31 aligned
+    __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
+    __host__ __device__ uint32_t group_log2() const { return (layer_flags >> 24) & 15u; }
+    __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
+};
+static_assert(sizeof(UTileDev) == 32, "UTileDev layout");
+
+// Byte offsets of everything inside the caller's workspace.
+struct WorkspaceLayout {
+    size_t layers = 0, ctiles = 0, utiles = 0;          // tables written by workspace_init
+    size_t tile_count = 0, tile_base = 0, tile_sum = 0; // per compress tile: words, first word in layer, sum of g_max
+    size_t layer_nsel = 0, layer_scale = 0;             // per layer
+    size_t gmax = 0, chunk_rel = 0;                     // per bin / per chunk
+    size_t stage = 0;                                   // uint16 per element: words before placement
+    size_t total = 0;
+};
+
+struct Plan {
+    uint32_t n_layers = 0;
+    uint32_t n_ctiles = 0, n_utiles = 0;
+    uint32_t n_bins_total = 0, n_chunks_total = 0;
+    uint64_t elem_span = 0;     // max over layers of elem_offset + n_elems
+    uint64_t n_elems_total = 0;
+    uint64_t fixed_bytes = 0;   // packet bytes before the first word
+    uint64_t bound_bytes = 0;   // packet bytes with every element sent
+    bool has_class[3] = {false, false, false};
+    uint64_t table_hash = 0;
+    WorkspaceLayout ws;
+    std::vector<LayerDev> layers;
+    std::vector<TileDev> ctiles;
+    std::vector<UTileDev> utiles;
+};
+
+// Validates the table (ADACOMP_E* on failure) and, with tables = true, fills the tile tables.
+int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &plan);
+uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers);
+uint32_t bin_magic(uint32_t L_T);
+int default_register_class();
+
+// ---- kernel launchers (adacomp_kernels.hip) ---------------------------------------------------
+struct CompressArgs {
+    const TileDev *tiles;
+    const LayerDev *layers;
+    const float *grad;
+    float *residue;
+    uint8_t *packet;
+    uint64_t capacity;
+    uint32_t *tile_count, *tile_base;
+    double *tile_sum;
+    uint32_t *layer_nsel;
+    float *layer_scale;
+    float *gmax;
+    uint32_t *chunk_rel;
+    uint16_t *stage;
+    uint32_t n_tiles, n_layers;
+    uint64_t fixed_bytes;
+};
+
+struct UnpackArgs {
+    const UTileDev *tiles;
+    const LayerDev *layers;
+    float *dense;
+    uint32_t n_tiles, n_layers, n_learners, accumulate;
+    const uint8_t *packets[kMaxPacketArgs];
+};
+
+int launch_fused(const CompressArgs &a, int jcode, void *stream);
+int launch_scan(const CompressArgs &a, void *stream);
+int launch_place(const CompressArgs &a, void *stream);
+int launch_unpack(const UnpackArgs &a, void *stream);
+int launch_copy(float *dst, const float *src, size_t n, void *stream);
+
+}  // namespace adacomp

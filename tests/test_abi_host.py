@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes agree with the container layout, and bad arguments give the documented codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import adacomp_workloads as W
+from paper_1712_02679_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1712_02679_amd import build
+        build.build()
+    return binding.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "adacomp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(adacomp_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_struct_sizes():
+    assert ctypes.sizeof(binding.Layer) == 24
+    assert binding.PACKET_HEADER.itemsize == 32 and binding.PACKET_LAYER.itemsize == 64
+
+
+def test_bin_index_constants(L):
+    assert binding.adacomp_selftest_binindex() == 0
+
+
+def test_sizes_follow_the_container_layout(L):
+    pad16 = lambda x: (x + 15) // 16 * 16
+    for i in range(1, 6):
+        t = W.workload(i).table()
+        fixed = 32 + 64 * len(t)
+        words = 0
+        for _, n, T in t:
+            wb = 1 if T <= 64 else 2
+            nb = -(-n // T)
+            fixed += pad16(nb * wb) + pad16(4 * (-(-nb // 64)))
+            words += pad16(n * wb)
+        assert binding.adacomp_packet_fixed_bytes(t) == fixed
+        assert binding.adacomp_packet_bound(t) == fixed + words
+        ws = binding.adacomp_workspace_bytes(t)
+        assert ws > 2 * W.workload(i).n_total and ws < 2.5 * W.workload(i).n_total + (1 << 20)
+
+
+def test_bad_tables_are_refused(L):
+    assert binding.adacomp_packet_bound([(0, 0, 50)]) == 0           # empty layer
+    assert binding.adacomp_packet_bound([(0, 10, 0)]) == 0           # L_T = 0
+    assert binding.adacomp_packet_bound([(0, 10, 16385)]) == 0       # L_T above 16K
+    assert binding.adacomp_packet_bound([(2, 10, 50)]) == 0          # offset not a multiple of 4
+    assert binding.adacomp_packet_bound([(0, 100, 50), (96, 8, 50)]) == 0   # overlap
+    assert binding.adacomp_packet_bound([(0, 1 << 31, 50)]) == 0     # layer too long
+    assert binding.adacomp_packet_bound([(0, 10, 16384)]) > 0
+    assert binding.adacomp_workspace_bytes([]) == 0
+
+
+def test_error_codes_without_touching_the_gpu(L):
+    t = binding.layer_array([(0, 1000, 50)])
+    buf = np.zeros(1 << 16, np.uint8)
+    base = (buf.ctypes.data + 255) // 256 * 256
+    p = ctypes.c_void_p
+    # compress on a workspace that was never initialised
+    rc = L.adacomp_compress(t, 1, p(base), p(base + 4096), p(base + 8192), 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EWORKSPACE
+    rc = L.adacomp_compress(t, 1, None, p(base + 4096), p(base + 8192), 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EINVAL
+    rc = L.adacomp_compress(t, 1, p(base + 4), p(base + 4096), p(base + 8192), 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EALIGN
+    rc = L.adacomp_compress(t, 1, p(base), p(base), p(base + 8192), 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EINVAL                                       # grad aliases residue
+    ptrs = (p * 1)(base)
+    rc = L.adacomp_unpack_accumulate(t, 1, ptrs, 1, p(base + 4096), p(base + 16384), 1 << 14, None)
+    assert rc == binding.EWORKSPACE
+    rc = L.adacomp_workspace_init(t, 1, p(base + 16384 + 8), 1 << 14, None)
+    assert rc == binding.EALIGN
+    rc = L.adacomp_workspace_init(t, 1, p(base + 16384), 16, None)
+    assert rc == binding.EWORKSPACE
+    assert L.adacomp_workspace_release(p(base)) == binding.EINVAL
+    assert b"L_T" in L.adacomp_strerror(binding.EBADLT)
+
+
+def test_no_cpu_fallback(L):
+    """Without a GPU the set-up call fails loudly instead of computing anything on the host."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    t = binding.layer_array([(0, 1000, 50)])
+    buf = np.zeros(1 << 16, np.uint8)
+    base = (buf.ctypes.data + 255) // 256 * 256
+    rc = L.adacomp_workspace_init(t, 1, ctypes.c_void_p(base), 1 << 15, None)
+    assert rc == binding.EHIP
