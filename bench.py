@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""bench.py -- throughput of the AdaComp pack/unpack hot path on one MI355X.
+
+One "step" is one mini-batch of the whole hot path on one GPU: every simulated learner runs
+adacomp_compress on its own gradient and residue (Algorithm 2 of the AdaComp paper), then one
+adacomp_unpack_accumulate sums all learners' packets into a dense gradient (unpack() of
+Algorithm 1).  Inputs are seeded synthetic gradients already resident in HBM when the clock starts.
+
+Prints ONE JSON line.  `value` = bytes of float32 gradient compressed and unpacked per second
+(n_learners * 4 * n_elems per step).  `roofline` prices the dominant kernel (k_fused, the
+streaming pass of compress) by its algorithmic bytes, 12 per element (read dW, read residue,
+write residue), against the MI355X's 8 TB/s HBM peak, with its duration measured by HIP events
+on the launch stream inside the timed region.  `cpu_baseline` times the CPU oracle, as it stands,
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_fused_hbm_traffic.txt")
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per k_fused launch from the committed rocprofv3 --pmc summary, if there is one
+    for this workload (lines 'workload: <name>' and 'traffic_bytes_per_launch: <int>')."""
+    try:
+        wl, val = None, None
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("workload:"):
+                wl = line.split(":", 1)[1].strip()
+            if line.startswith("traffic_bytes_per_launch:") and wl == workload_name:
+                val = int(float(line.split(":", 1)[1]))
+        return val
+    except OSError:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5, help="1..5 (5 = speech-DNN FC stack, the metric's configuration)")
+    ap.add_argument("--learners", type=int, default=0, help="override the workload's learner count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (simulated learners are separate buffers on "
+                 "one device; there is no collective path) -- use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import adacomp_workloads as W
+    import paper_1712_02679_amd as A
+    from paper_1712_02679_amd import binding
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; libadacomp has no CPU path")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = W.workload(args.workload)
+    n_learners = args.learners or wl.n_learners
+    table, n_total, n_params = wl.table(), wl.n_total, wl.n_params
+    K, Wm = args.steps, args.warmup
+    threads = min(16, os.cpu_count() or 1)
+
+    # ---- inputs: one seeded gradient buffer per learner; learner k uses buffer (k + t) mod n at
+    #      step t, so every learner sees a fresh draw each step and a step never uses a buffer twice
+    t0 = time.time()
+    grads = []
+    for i in range(n_learners):
+        g = W.gradient(wl, i, 0, seed=0, threads=threads)
+        grads.append(torch.from_numpy(g).to(dev))
+    log(f"{wl.name}: {n_params} elements x {n_learners} learners generated and uploaded in {time.time() - t0:.1f}s")
+
+    ws = torch.zeros(A.adacomp_workspace_bytes(table), dtype=torch.uint8, device=dev)
+    A.adacomp_workspace_init(table, ws)
+    bound = A.adacomp_packet_bound(table)
+    residue = [torch.zeros(n_total, dtype=torch.float32, device=dev) for _ in range(n_learners)]
+    packets = [torch.zeros(bound, dtype=torch.uint8, device=dev) for _ in range(n_learners)]
+    dense = torch.zeros(n_total, dtype=torch.float32, device=dev)
+    layers_c = binding.layer_array(table)
+
+    L = binding.lib()
+    import ctypes
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ws_p, ws_n = ctypes.c_void_p(ws.data_ptr()), ws.numel()
+    pk_ptrs = (ctypes.c_void_p * n_learners)(*[p.data_ptr() for p in packets])
+
+    def compress_all(t):
+        for k in range(n_learners):
+            rc = L.adacomp_compress(layers_c, len(table), ctypes.c_void_p(grads[(k + t) % n_learners].data_ptr()),
+                                    ctypes.c_void_p(residue[k].data_ptr()), ctypes.c_void_p(packets[k].data_ptr()),
+                                    bound, ws_p, ws_n, stream)
+            if rc:
+                raise RuntimeError(f"adacomp_compress: {rc}")
+
+    def unpack_all():
+        rc = L.adacomp_unpack_accumulate(layers_c, len(table), pk_ptrs, n_learners,
+                                         ctypes.c_void_p(dense.data_ptr()), ws_p, ws_n, stream)
+        if rc:
+            raise RuntimeError(f"adacomp_unpack_accumulate: {rc}")
+
+    # ---- warm-up on the same buffers, then residues back to zero (training start) ---------------
+    for t in range(Wm):
+        compress_all(t)
+        unpack_all()
+    torch.cuda.synchronize()
+    for r in residue:
+        r.zero_()
+    torch.cuda.synchronize()
+
+    # ---- timed region ------------------------------------------------------------------------------
+    use_events = not args.no_kernel_events
+    A.adacomp_timing_enable(use_events)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for t in range(K):
+        ev[t][0].record()
+        compress_all(t)
+        ev[t][1].record()
+        unpack_all()
+        ev[t][2].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    fused_ms, fused_n = A.adacomp_timing_read() if use_events else (0.0, 0)
+    A.adacomp_timing_enable(False)
+
+    compress_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in range(K)) / K
+    unpack_ms = sum(ev[t][1].elapsed_time(ev[t][2]) for t in range(K)) / K
+    ms_per_step = elapsed * 1e3 / K
+    grad_bytes_per_step = n_learners * 4 * n_params
+    value = grad_bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---- compression achieved at the last timed step (headers only: tiny copies) -------------------
+    n_sel = total_bytes = 0
+    paper_bits = 0
+    for p in packets:
+        head, recs = A.read_packet_summary(p)
+        assert int(head["status"]) == 0
+        n_sel += int(head["n_selected"])
+        total_bytes += int(head["total_bytes"])
+        paper_bits += int(sum(int(r["word_bits"]) * int(r["n_selected"]) for r in recs))
+    packet_bytes_mean = total_bytes / n_learners
+    ratio_paper = 32.0 * n_params * n_learners / max(1, paper_bits)
+    ratio_wire = 4.0 * n_params * n_learners / max(1, total_bytes)
+
+    # ---- roofline of the dominant kernel ------------------------------------------------------------
+    alg_bytes_launch = 12 * n_params  # k_fused: read dW, read residue, write residue, 4 B each
+    roofline = None
+    if use_events and fused_n:
+        dur_ms = fused_ms / fused_n
+        achieved = alg_bytes_launch / (dur_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_fused", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": measured_traffic(wl.name), "algorithmic_bytes_per_launch": alg_bytes_launch,
+                    "avg_launch_ms": round(dur_ms, 5), "launches": int(fused_n)}
+    # whole step by algorithmic bytes: n * (12 N + P) + 4 N + n * P
+    step_alg_bytes = n_learners * (12 * n_params + packet_bytes_mean) + 4 * n_params + n_learners * packet_bytes_mean
+    step_frac = step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    # ---- CPU oracle on a bounded sample ----------------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.Oracle()
+        # as many learners of step 0 as fit in about 12 s of single-thread oracle time (at least
+        # 2), then one unpack of their packets: the call mix of one GPU step, on fewer learners
+        budget_s, n_cpu, pk, dt = 12.0, 0, [], 0.0
+        while n_cpu < n_learners and (n_cpu < 2 or dt < budget_s):
+            g_host = grads[n_cpu].cpu().numpy()
+            r_host = np.zeros(n_total, np.float32)
+            t1 = time.perf_counter()
+            pk.append(orc.compress(table, g_host, r_host))
+            dt += time.perf_counter() - t1
+            n_cpu += 1
+        t1 = time.perf_counter()
+        orc.unpack_accumulate(table, pk, n_total)
+        dt += time.perf_counter() - t1
+        cpu = {"value": round(n_cpu * 4 * n_params / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} learner(s) x 1 step of {wl.name} (compress each, then one unpack of "
+                         f"{n_cpu} packets), single thread, {dt:.1f}s of oracle time"}
+
+    out = {
+        "metric": "GB/s gradient compressed+unpacked", "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name} (configuration {wl.index}): {len(table)} layers, {n_params} fp32 elements, "
+                               f"L_T {sorted(set(l[2] for l in table))}, {n_learners} simulated learners, residues start at zero",
+                   "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "hbm_frac_step_algorithmic": round(step_frac, 4),
+        "compress_ms_per_step": round(compress_ms, 4), "unpack_ms_per_step": round(unpack_ms, 4),
+        "compression": {"paper_accounting": round(ratio_paper, 2), "wire": round(ratio_wire, 2),
+                        "selected_per_learner_last_step": n_sel // n_learners,
+                        "packet_bytes_mean_last_step": int(packet_bytes_mean),
+                        "paper_context": "~40x conv / ~200x FC-LSTM on trained gradients"},
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

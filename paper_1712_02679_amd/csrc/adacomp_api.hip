@@ -139,7 +139,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
 
         // ---- unpack tiles: a power-of-two number of bins inside one 64-bin chunk, or slices of
         //      one long bin --------------------------------------------------------------------
-        const uint32_t glog = T <= 64 ? 4u : 6u;      // lanes that share a bin: 16 or 64
+        const uint32_t glog = T <= 64 ? 3u : 4u;      // lanes that share a bin: 8 or 16
         if (T <= kUnpackTileElems) {
             uint32_t nb = 1;
             while (nb * 2 <= ADACOMP_CHUNK_BINS && uint64_t(nb) * 2 * T <= kUnpackTileElems) nb *= 2;
@@ -201,7 +201,8 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     w.layer_scale = off; off = pad256(off + 4 * size_t(n_layers));
     w.gmax = off;        off = pad256(off + 4 * size_t(p.n_bins_total));
     w.chunk_rel = off;   off = pad256(off + 4 * size_t(p.n_chunks_total));
-    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span));
+    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span) + 64);  // slack: k_place reads 16 entries ahead
+    w.stage_g = off;     off = pad256(off + 4 * size_t(p.elem_span) + 64);
     w.total = off;
     return ADACOMP_OK;
 }
@@ -334,6 +335,7 @@ int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const flo
     a.gmax = reinterpret_cast<float *>(ws + p.ws.gmax);
     a.chunk_rel = reinterpret_cast<uint32_t *>(ws + p.ws.chunk_rel);
     a.stage = reinterpret_cast<uint16_t *>(ws + p.ws.stage);
+    a.stage_g = reinterpret_cast<uint32_t *>(ws + p.ws.stage_g);
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
     a.fixed_bytes = p.fixed_bytes;

@@ -12,7 +12,7 @@
 //            the packet, g_max and its per-tile float64 sum go to scratch.
 //   k_scan   one workgroup per layer: the layer scale = average of the g_max vector (section
 //            "Pseudo code") and the exclusive scan of per-tile word counts.
-//   k_place  one wave per tile: moves the staged entries to their final place in the packet as
+//   k_place  16 lanes per tile: moves the staged entries to their final place in the packet as
 //            (index-in-bin, ternary code) words and applies the only step that needs the
 //            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
 //            about 1-10 % of the elements); one extra workgroup writes header and records.
@@ -26,18 +26,29 @@
 namespace adacomp {
 
 // ---- small device helpers --------------------------------------------------------------------
+// Streaming (non-temporal) 16-byte accesses: every element of dW and the residue is touched once
+// per call, so nothing is gained by keeping it in L2, and on MI355X the streaming hint is worth
+// about 15 % of bandwidth on a read-read-write pass.
+typedef float vfloat4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ vfloat4 load_stream4(const float *p) { return __builtin_nontemporal_load(reinterpret_cast<const vfloat4 *>(p)); }
+__device__ __forceinline__ void store_stream4(float *p, vfloat4 v) { __builtin_nontemporal_store(v, reinterpret_cast<vfloat4 *>(p)); }
+
 __device__ __forceinline__ uint32_t bin_of(uint32_t e, uint32_t L_T, uint32_t magic)
 {
     return L_T == 1u ? e : __umulhi(e, magic);
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS traffic): four
+// shift-and-add steps inside each row of 16 lanes, then the row totals are carried over with the
+// two row broadcasts (lane 15 of rows 0 and 2 into rows 1 and 3, lane 31 into rows 2 and 3).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t /*lane*/)
 {
-#pragma unroll
-    for (uint32_t d = 1; d < 64; d <<= 1) {
-        uint32_t t = __shfl_up(v, d, 64);
-        if (lane >= d) v += t;
-    }
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x111, 0xF, 0xF, false));  // row_shr:1
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x112, 0xF, 0xF, false));  // row_shr:2
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x114, 0xF, 0xF, false));  // row_shr:4
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x118, 0xF, 0xF, false));  // row_shr:8
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x142, 0xA, 0xF, false));  // row_bcast:15 -> rows 1, 3
+    v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x143, 0xC, 0xF, false));  // row_bcast:31 -> rows 2, 3
     return v;
 }
 
@@ -99,8 +110,8 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     for (int j = 0; j < J; ++j) {
         const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
         if (vec && e0 + 4u <= n) {
-            const float4 rv = *reinterpret_cast<const float4 *>(rs + e0);
-            const float4 wv = *reinterpret_cast<const float4 *>(gr + e0);
+            const vfloat4 rv = load_stream4(rs + e0);
+            const vfloat4 wv = load_stream4(gr + e0);
             r[j][0] = rv.x; r[j][1] = rv.y; r[j][2] = rv.z; r[j][3] = rv.w;
             w[j][0] = wv.x; w[j][1] = wv.y; w[j][2] = wv.z; w[j][3] = wv.w;
         } else {
@@ -127,7 +138,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
             mb[j][c] = ag > ah ? ag : ah;
         }
         if (vec && e0 + 4u <= n) {
-            *reinterpret_cast<float4 *>(rs + e0) = make_float4(G[0], G[1], G[2], G[3]);
+            store_stream4(rs + e0, vfloat4{G[0], G[1], G[2], G[3]});
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -197,6 +208,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 
     // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
     uint16_t *__restrict__ stage = a.stage + td.elem_base;
+    uint32_t *__restrict__ stage_g = a.stage_g + td.elem_base;  // G of the sent elements, for k_place
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
@@ -209,6 +221,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
                     const uint32_t e = e0 + uint32_t(c);
                     const uint32_t code = (gb[j][c] >> 31) ? 3u : 1u;  // ternary value: -scale / +scale
                     stage[pos] = uint16_t((e << 2) | code);
+                    stage_g[pos] = gb[j][c];
                     ++pos;
                     atomicAdd(&s_cnt[bin_of(e, T, M)], 1u);
                 }
@@ -252,9 +265,12 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 
 // ==============================================================================================
 // k_scan: per layer, scale = (sum of g_max) / n_bins in float64 rounded once to float32, and the
-// exclusive scan of the tiles' word counts.
+// exclusive scan of the tiles' word counts.  One workgroup of 1024 threads per layer; a thread
+// owns a contiguous run of tiles so that its loads are independent and issue back to back.
 // ==============================================================================================
-__global__ __launch_bounds__(kWG) void k_scan(const CompressArgs a)
+constexpr uint32_t kScanWG = 1024;
+
+__global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
 {
     const uint32_t l = blockIdx.x;
     if (l >= a.n_layers) return;
@@ -262,15 +278,16 @@ __global__ __launch_bounds__(kWG) void k_scan(const CompressArgs a)
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
     const uint32_t nt = ld.n_ctiles, ts = ld.ctile_start;
-    const uint32_t per = (nt + kWG - 1) / kWG;
+    const uint32_t per = (nt + kScanWG - 1) / kScanWG;
     const uint32_t lo = tid * per < nt ? tid * per : nt;
     const uint32_t hi = lo + per < nt ? lo + per : nt;
 
-    __shared__ uint32_t s_wsum[4];
-    __shared__ double s_dsum[4];
+    __shared__ uint32_t s_wsum[16];
+    __shared__ double s_dsum[16];
 
     uint32_t csum = 0u;
     double dsum = 0.0;
+#pragma unroll 8
     for (uint32_t i = lo; i < hi; ++i) { csum += a.tile_count[ts + i]; dsum += a.tile_sum[ts + i]; }
 
     const uint32_t incl = wave_incl_scan(csum, lane);
@@ -281,24 +298,30 @@ __global__ __launch_bounds__(kWG) void k_scan(const CompressArgs a)
     uint32_t wave_base = 0u;
     for (uint32_t wv = 0; wv < wave; ++wv) wave_base += s_wsum[wv];
     uint32_t run = wave_base + incl - csum;
+#pragma unroll 8
     for (uint32_t i = lo; i < hi; ++i) { a.tile_base[ts + i] = run; run += a.tile_count[ts + i]; }
     if (tid == 0) {
-        const double total = ((s_dsum[0] + s_dsum[1]) + s_dsum[2]) + s_dsum[3];
+        double total = 0.0;
+        uint32_t nsel = 0u;
+        for (uint32_t wv = 0; wv < kScanWG / 64u; ++wv) { total += s_dsum[wv]; nsel += s_wsum[wv]; }
         a.layer_scale[l] = float(total / double(ld.n_bins));
-        a.layer_nsel[l] = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+        a.layer_nsel[l] = nsel;
     }
 }
 
 // ==============================================================================================
 // k_place: staged entries -> final words; residue <- G - Gq at the sent elements; chunk offsets;
-// header, records and padding (last workgroup).
+// header, records and padding (last workgroup).  A tile sends a few dozen words at most in
+// steady state, so 16 lanes serve a tile and a workgroup serves 16 tiles; the whole grid is
+// resident at once and the kernel costs about three dependent memory round trips.
 // ==============================================================================================
 __device__ __forceinline__ uint64_t pad16_dev(uint64_t x) { return (x + 15u) & ~uint64_t(15); }
+constexpr uint32_t kPlaceLanes = 16;
+constexpr uint32_t kPlaceTiles = kWG / kPlaceLanes;
 
 __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 {
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+    const uint32_t tid = threadIdx.x;
 
     if (blockIdx.x == gridDim.x - 1) {
         // ---- header, layer records, zero padding ------------------------------------------------
@@ -337,48 +360,66 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
         return;
     }
 
-    const uint32_t tile = blockIdx.x * 4u + wave;
+    const uint32_t sub = tid & (kPlaceLanes - 1u);
+    const uint32_t tile = blockIdx.x * kPlaceTiles + (tid / kPlaceLanes);
     if (tile >= a.n_tiles) return;
     const TileDev td = a.tiles[tile];
     const uint32_t l = td.layer();
-    const LayerDev ld = a.layers[l];
+
+    // independent loads first: the tile's counters, its first staged entries, the layer's fields
+    const uint32_t cnt = a.tile_count[tile], base = a.tile_base[tile];
+    const uint16_t *__restrict__ stage = a.stage + td.elem_base;
+    float *__restrict__ rs = a.residue + td.elem_base;
+    const uint32_t *__restrict__ stage_g = a.stage_g + td.elem_base;
+    const uint32_t s_first = stage[sub];  // speculative: the staging arrays have 16 entries of slack
+    const uint32_t g_first = stage_g[sub];
+    const float scale = a.layer_scale[l];
+    const uint32_t wbytes = a.layers[l].word_bytes;
+    const uint64_t chunks_offset = a.layers[l].chunks_offset;
+    const uint32_t chunk_start = a.layers[l].chunk_start;
 
     // first word of this layer = end of the fixed part + the (padded) word sections before it
     uint64_t woff = 0;
-    for (uint32_t m = lane; m < l; m += 64u) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
-    woff = wave_sum64(woff) + a.fixed_bytes;
+    for (uint32_t m = sub; m < l; m += kPlaceLanes) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
+#pragma unroll
+    for (uint32_t d = kPlaceLanes / 2; d > 0; d >>= 1) {
+        const uint32_t lo = __shfl_xor(uint32_t(woff), d, kPlaceLanes), hi = __shfl_xor(uint32_t(woff >> 32), d, kPlaceLanes);
+        woff += (uint64_t(hi) << 32) | lo;
+    }
+    woff += a.fixed_bytes;
 
-    const uint32_t cnt = a.tile_count[tile], base = a.tile_base[tile];
-    const float scale = a.layer_scale[l];
-    const uint16_t *__restrict__ stage = a.stage + td.elem_base;
-    float *__restrict__ rs = a.residue + td.elem_base;
     const uint32_t T = td.L_T, M = td.magic;
-
-    for (uint32_t p = lane; p < cnt; p += 64u) {
-        const uint32_t s = stage[p];
+    for (uint32_t p = sub; p < cnt; p += kPlaceLanes) {
+        const uint32_t s = p == sub ? s_first : uint32_t(stage[p]);
+        const float g = __uint_as_float(p == sub ? g_first : stage_g[p]);
         const uint32_t e = s >> 2, code = s & 3u;
         const uint32_t b = bin_of(e, T, M);
         const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
-        const uint64_t at = woff + uint64_t(base + p) * ld.word_bytes;
-        if (at + ld.word_bytes <= a.capacity) {
-            if (ld.word_bytes == 1u) a.packet[at] = uint8_t(word);
+        const uint64_t at = woff + uint64_t(base + p) * wbytes;
+        if (at + wbytes <= a.capacity) {
+            if (wbytes == 1u) a.packet[at] = uint8_t(word);
             else *reinterpret_cast<uint16_t *>(a.packet + at) = uint16_t(word);
         }
-        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left there
-        const float g = rs[e];
+        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale.  G comes from the staging
+        // area, so this is a 4-byte store and the residue line is not read back
         rs[e] = code == 1u ? g - scale : g + scale;
     }
 
     // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
     const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
-    for (uint32_t t = t0 + 64u * lane; t < td.n_bins; t += 64u * 64u) {
+    for (uint32_t t = t0 + 64u * sub; t < td.n_bins; t += 64u * kPlaceLanes) {
         const uint32_t c = (td.first_bin + t) >> 6;
-        reinterpret_cast<uint32_t *>(a.packet + ld.chunks_offset)[c] = base + a.chunk_rel[ld.chunk_start + c];
+        reinterpret_cast<uint32_t *>(a.packet + chunks_offset)[c] = base + a.chunk_rel[chunk_start + c];
     }
 }
 
 // ==============================================================================================
 // k_unpack: dense_out <- sum over learners, in learner order, of the decoded packets.
+// A workgroup owns a tile of the output in LDS.  Per group of 16 learners it first gathers, for
+// every (learner, bin) of the tile, where the bin's words start (all learners' loads in flight
+// together), then a lane group per bin fetches the words of all 16 learners before adding them in
+// learner order.  The adds to one LDS address come from one wave in program order, so the sum
+// order is fixed without atomics.
 // ==============================================================================================
 __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 {
@@ -390,11 +431,12 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
     const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
     const bool vec = ut.aligned();
+    const bool w8 = ld.word_bytes == 1u;
     float *__restrict__ out = a.dense + ut.elem_base;
 
     __shared__ float s_acc[kUnpackTileElems];
     __shared__ uint32_t s_start[kLearnerGroup][64];  // first word of (learner, bin) inside the layer's words
-    __shared__ uint32_t s_cnt[kLearnerGroup][64];
+    __shared__ uint16_t s_cnt[kLearnerGroup][64];
     __shared__ float s_scale[kLearnerGroup];
     __shared__ uint64_t s_words[kLearnerGroup];      // address of the layer's first word
 
@@ -414,55 +456,94 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
     }
 
     const uint32_t chunk = ut.first_bin >> 6;
-    const uint32_t chunk_bin0 = chunk << 6;
+    const uint32_t b = (chunk << 6) + lane;           // the bin this lane looks up in phase 1
+    const bool in_scan = b < ut.first_bin + nb;       // bins of the chunk up to the end of the tile
+    const bool in_tile = in_scan && b >= ut.first_bin;
     const uint32_t glog = ut.group_log2(), gsz = 1u << glog;
+    constexpr uint32_t kPerWave = kLearnerGroup / 4u;
 
     for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
         const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
         __syncthreads();  // accumulators initialised / previous group finished with the tables
 
-        // ---- per learner: where each bin's words start (one wave per learner) ------------------
-        for (uint32_t kk = wave; kk < nk; kk += 4u) {
-            const uint8_t *pk = a.packets[k0 + kk];
-            const adacomp_packet_header_t *h = reinterpret_cast<const adacomp_packet_header_t *>(pk);
-            const bool ok = h->magic == ADACOMP_PACKET_MAGIC && h->version == ADACOMP_PACKET_VERSION &&
-                            h->status == ADACOMP_STATUS_COMPLETE && h->n_layers == a.n_layers;
-            const adacomp_packet_layer_t *rec =
-                reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
-            const uint32_t b = chunk_bin0 + lane;
-            const bool mine = ok && b < ut.first_bin + nb;
-            uint32_t c = 0u;
-            if (mine) c = ld.word_bytes == 1u ? uint32_t(pk[ld.counts_offset + b])
-                                              : uint32_t(reinterpret_cast<const uint16_t *>(pk + ld.counts_offset)[b]);
-            const uint32_t incl = wave_incl_scan(c, lane);
-            const uint32_t coff = ok ? reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk] : 0u;
-            if (b >= ut.first_bin && b < ut.first_bin + nb) {
-                s_start[kk][b - ut.first_bin] = coff + incl - c;
-                s_cnt[kk][b - ut.first_bin] = c;
+        // ---- phase 1: wave w serves learners w, w + 4, ...; all their loads are issued first ----
+        uint32_t c[kPerWave], coff[kPerWave];
+        bool ok[kPerWave];
+#pragma unroll
+        for (uint32_t q = 0; q < kPerWave; ++q) {
+            const uint32_t kk = wave + 4u * q;
+            c[q] = 0u; coff[q] = 0u; ok[q] = false;
+            if (kk < nk) {
+                const uint8_t *pk = a.packets[k0 + kk];
+                const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers in one load
+                ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
+                        (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
+                // counts and chunk offsets sit in the fixed part, which every packet buffer holds
+                if (in_scan) c[q] = w8 ? uint32_t(pk[ld.counts_offset + b])
+                                       : uint32_t(reinterpret_cast<const uint16_t *>(pk + ld.counts_offset)[b]);
+                coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
+                if (lane == 0) {
+                    const adacomp_packet_layer_t *rec =
+                        reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
+                    s_scale[kk] = rec->scale;
+                    s_words[kk] = uint64_t(reinterpret_cast<uintptr_t>(pk)) + rec->words_offset;
+                }
             }
-            if (lane == 0) {
-                s_scale[kk] = ok ? rec->scale : 0.f;
-                s_words[kk] = ok ? uint64_t(reinterpret_cast<uintptr_t>(pk + rec->words_offset)) : 0ull;
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kPerWave; ++q) {
+            const uint32_t kk = wave + 4u * q;
+            if (kk < nk) {
+                const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
+                const uint32_t incl = wave_incl_scan(cq, lane);
+                if (in_tile) {
+                    s_start[kk][b - ut.first_bin] = coff[q] + incl - cq;
+                    s_cnt[kk][b - ut.first_bin] = uint16_t(cq);
+                }
             }
         }
         __syncthreads();
 
-        // ---- a lane group owns a bin and adds its learners' values in learner order.  The adds to
-        //      one LDS address all come from one wave in program order, so the order is fixed. ----
+        // ---- phase 2: a lane group owns a bin --------------------------------------------------
         for (uint32_t s = tid; s < (nb << glog); s += kWG) {
             const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
             const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
             float *acc = s_acc + lb * T;
-            for (uint32_t kk = 0; kk < nk; ++kk) {
-                const uint32_t c = s_cnt[kk][lb], st = s_start[kk][lb];
-                const float sc = s_scale[kk];
-                const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
-                for (uint32_t jw = sub; jw < c; jw += gsz) {
-                    const uint32_t word = ld.word_bytes == 1u ? uint32_t(wp[st + jw])
-                                                              : uint32_t(reinterpret_cast<const uint16_t *>(wp)[st + jw]);
-                    const uint32_t idx = (word >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
-                    const uint32_t code = word & 3u;
-                    if (idx < span && (code & 1u)) acc[idx] += code == 1u ? sc : -sc;
+            uint32_t word[kLearnerGroup];
+            bool big = false;
+#pragma unroll
+            for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
+                word[kk] = 0u;
+                if (kk < nk) {
+                    const uint32_t cc = s_cnt[kk][lb];
+                    big |= cc > gsz;
+                    if (sub < cc) {
+                        const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
+                        const uint32_t at = s_start[kk][lb] + sub;
+                        word[kk] = w8 ? uint32_t(wp[at]) : uint32_t(reinterpret_cast<const uint16_t *>(wp)[at]);
+                    }
+                }
+            }
+            if (!big) {
+#pragma unroll
+                for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
+                    const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
+                    const uint32_t code = word[kk] & 3u;
+                    if ((code & 1u) && idx < span) acc[idx] += code == 1u ? s_scale[kk] : -s_scale[kk];
+                }
+            } else {
+                // some learner sends more words from this bin than the group has lanes: plain loops,
+                // one learner after the other (same order)
+                for (uint32_t kk = 0; kk < nk; ++kk) {
+                    const uint32_t cc = s_cnt[kk][lb], st = s_start[kk][lb];
+                    const float sc = s_scale[kk];
+                    const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
+                    for (uint32_t jw = sub; jw < cc; jw += gsz) {
+                        const uint32_t wd = w8 ? uint32_t(wp[st + jw]) : uint32_t(reinterpret_cast<const uint16_t *>(wp)[st + jw]);
+                        const uint32_t idx = (wd >> 2) - ut.idx_lo;
+                        const uint32_t code = wd & 3u;
+                        if ((code & 1u) && idx < span) acc[idx] += code == 1u ? sc : -sc;
+                    }
                 }
             }
         }
@@ -471,7 +552,7 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
         const float4 v = *reinterpret_cast<const float4 *>(&s_acc[i]);
-        if (vec && i + 4u <= n) *reinterpret_cast<float4 *>(out + i) = v;
+        if (vec && i + 4u <= n) store_stream4(out + i, vfloat4{v.x, v.y, v.z, v.w});
         else {
             out[i] = v.x;
             if (i + 1u < n) out[i + 1] = v.y;
@@ -507,13 +588,13 @@ int launch_fused(const CompressArgs &a, int jcode, void *stream)
 
 int launch_scan(const CompressArgs &a, void *stream)
 {
-    hipLaunchKernelGGL(k_scan, dim3(a.n_layers), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(k_scan, dim3(a.n_layers), dim3(kScanWG), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }
 
 int launch_place(const CompressArgs &a, void *stream)
 {
-    hipLaunchKernelGGL(k_place, dim3((a.n_tiles + 3u) / 4u + 1u), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(k_place, dim3((a.n_tiles + kPlaceTiles - 1u) / kPlaceTiles + 1u), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }
 

@@ -66,6 +66,7 @@ struct WorkspaceLayout {
     size_t layer_nsel = 0, layer_scale = 0;             // per layer
     size_t gmax = 0, chunk_rel = 0;                     // per bin / per chunk
     size_t stage = 0;                                   // uint16 per element: words before placement
+    size_t stage_g = 0;                                 // float per element: G of the staged words
     size_t total = 0;
 };
 
@@ -106,6 +107,7 @@ struct CompressArgs {
     float *gmax;
     uint32_t *chunk_rel;
     uint16_t *stage;
+    uint32_t *stage_g;
     uint32_t n_tiles, n_layers;
     uint64_t fixed_bytes;
 };
