@@ -115,6 +115,17 @@ def main():
         if rc:
             raise RuntimeError(f"adacomp_unpack_accumulate: {rc}")
 
+    # ---- plain device copy of one gradient (8 B per element): the calibration kernel for the HBM
+    #      byte counters, and the copy bandwidth this GPU reaches, for context ----------------------
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    A.adacomp_copy_f32(dense, grads[0], n_total)
+    c0.record()
+    for _ in range(5):
+        A.adacomp_copy_f32(dense, grads[0], n_total)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 8.0 * n_total * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+
     # ---- warm-up on the same buffers, then residues back to zero (training start) ---------------
     for t in range(Wm):
         compress_all(t)
@@ -205,7 +216,7 @@ def main():
                    "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "hbm_frac_step_algorithmic": round(step_frac, 4),
+        "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),
         "compress_ms_per_step": round(compress_ms, 4), "unpack_ms_per_step": round(unpack_ms, 4),
         "compression": {"paper_accounting": round(ratio_paper, 2), "wire": round(ratio_wire, 2),
                         "selected_per_learner_last_step": n_sel // n_learners,
