@@ -56,6 +56,10 @@ def main():
     ap.add_argument("--learners", type=int, default=0, help="override the workload's learner count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
+    ap.add_argument("--batch", choices=["auto", "on", "off"], default="auto",
+                    help="on: one adacomp_compress_batch call per step; off: one adacomp_compress call per learner; "
+                         "auto: batch when the gradient is below 64 M elements (launch-bound workloads), single "
+                         "calls above (the streaming kernel sustains a higher rate in launches of one learner)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (simulated learners are separate buffers on "
@@ -76,6 +80,7 @@ def main():
     n_learners = args.learners or wl.n_learners
     table, n_total, n_params = wl.table(), wl.n_total, wl.n_params
     K, Wm = args.steps, args.warmup
+    args.no_batch = args.batch == "off" or (args.batch == "auto" and n_params >= 64_000_000)
     threads = min(16, os.cpu_count() or 1)
 
     # ---- inputs: one seeded gradient buffer per learner; learner k uses buffer (k + t) mod n at
@@ -87,7 +92,7 @@ def main():
         grads.append(torch.from_numpy(g).to(dev))
     log(f"{wl.name}: {n_params} elements x {n_learners} learners generated and uploaded in {time.time() - t0:.1f}s")
 
-    ws = torch.zeros(A.adacomp_workspace_bytes(table), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(A.adacomp_workspace_bytes_batch(table, n_learners), dtype=torch.uint8, device=dev)
     A.adacomp_workspace_init(table, ws)
     bound = A.adacomp_packet_bound(table)
     residue = [torch.zeros(n_total, dtype=torch.float32, device=dev) for _ in range(n_learners)]
@@ -101,7 +106,18 @@ def main():
     ws_p, ws_n = ctypes.c_void_p(ws.data_ptr()), ws.numel()
     pk_ptrs = (ctypes.c_void_p * n_learners)(*[p.data_ptr() for p in packets])
 
+    vp = ctypes.c_void_p
+    res_ptrs = (vp * n_learners)(*[r.data_ptr() for r in residue])
+    grad_ptrs = [(vp * n_learners)(*[grads[(k + t) % n_learners].data_ptr() for k in range(n_learners)])
+                 for t in range(n_learners)]
+
     def compress_all(t):
+        if not args.no_batch:
+            rc = L.adacomp_compress_batch(layers_c, len(table), n_learners, grad_ptrs[t % n_learners], res_ptrs,
+                                          pk_ptrs, bound, ws_p, ws_n, stream)
+            if rc:
+                raise RuntimeError(f"adacomp_compress_batch: {rc}")
+            return
         for k in range(n_learners):
             rc = L.adacomp_compress(layers_c, len(table), ctypes.c_void_p(grads[(k + t) % n_learners].data_ptr()),
                                     ctypes.c_void_p(residue[k].data_ptr()), ctypes.c_void_p(packets[k].data_ptr()),
@@ -155,6 +171,8 @@ def main():
     compress_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in range(K)) / K
     unpack_ms = sum(ev[t][1].elapsed_time(ev[t][2]) for t in range(K)) / K
     ms_per_step = elapsed * 1e3 / K
+    log("per step compress ms: " + " ".join(f"{ev[t][0].elapsed_time(ev[t][1]):.3f}" for t in range(K)))
+    log("per step unpack   ms: " + " ".join(f"{ev[t][1].elapsed_time(ev[t][2]):.3f}" for t in range(K)))
     grad_bytes_per_step = n_learners * 4 * n_params
     value = grad_bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
@@ -172,14 +190,16 @@ def main():
     ratio_wire = 4.0 * n_params * n_learners / max(1, total_bytes)
 
     # ---- roofline of the dominant kernel ------------------------------------------------------------
-    alg_bytes_launch = 12 * n_params  # k_fused: read dW, read residue, write residue, 4 B each
+    per_launch = 1 if args.no_batch else n_learners  # learners one k_fused launch covers
+    alg_bytes_launch = 12 * n_params * per_launch  # k_fused: read dW, read residue, write residue, 4 B each
     roofline = None
     if use_events and fused_n:
         dur_ms = fused_ms / fused_n
         achieved = alg_bytes_launch / (dur_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_fused", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": measured_traffic(wl.name), "algorithmic_bytes_per_launch": alg_bytes_launch,
+                    "traffic": (measured_traffic(wl.name) or 0) * per_launch or None,
+                    "algorithmic_bytes_per_launch": alg_bytes_launch, "learners_per_launch": per_launch,
                     "avg_launch_ms": round(dur_ms, 5), "launches": int(fused_n)}
     # whole step by algorithmic bytes: n * (12 N + P) + 4 N + n * P
     step_alg_bytes = n_learners * (12 * n_params + packet_bytes_mean) + 4 * n_params + n_learners * packet_bytes_mean
@@ -213,7 +233,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name} (configuration {wl.index}): {len(table)} layers, {n_params} fp32 elements, "
                                f"L_T {sorted(set(l[2] for l in table))}, {n_learners} simulated learners, residues start at zero",
-                   "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0},
+                   "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0,
+                   "compress_call": "adacomp_compress" if args.no_batch else "adacomp_compress_batch"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),

@@ -54,7 +54,8 @@ extern "C" {
 #endif
 
 #define ADACOMP_OK 0
-#define ADACOMP_EINVAL (-1)     /* null pointer, n_layers == 0, n_elems == 0 or >= 2^31, overlapping layers */
+#define ADACOMP_EINVAL (-1)     /* null pointer, n_layers == 0, n_elems == 0 or >= 2^31, overlapping layers,
+                                   or a table whose adacomp_packet_bound would reach 4 GiB             */
 #define ADACOMP_EBADLT (-2)     /* L_T == 0 or L_T > 16384                                               */
 #define ADACOMP_EALIGN (-3)     /* elem_offset not a multiple of 4, or a buffer not 16-byte aligned      */
 #define ADACOMP_ENOSPC (-4)     /* packet_capacity below the fixed part of the packet                    */
@@ -104,6 +105,10 @@ size_t adacomp_packet_fixed_bytes(const adacomp_layer_t *layers, uint32_t n_laye
  * tables, per-bin g_max, per-tile counters, staging for unplaced words). 0 if the table is invalid. */
 size_t adacomp_workspace_bytes(const adacomp_layer_t *layers, uint32_t n_layers);
 
+/* Same, for adacomp_compress_batch with up to n_learners learners per call: the tables once plus
+ * one scratch block per learner (about 2 bytes per gradient element each). */
+size_t adacomp_workspace_bytes_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners);
+
 /* ---- set-up --------------------------------------------------------------------------------- */
 
 /* Writes the device-side tile tables for this layer table into the head of `workspace`
@@ -133,6 +138,18 @@ int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const flo
                      float *residue, void *packet_out, size_t packet_capacity, void *workspace,
                      size_t workspace_bytes, void *hip_stream);
 
+/* pack() for several learners that share one layer table, in one set of launches (the simulated
+ * learners of a single-GPU run, or several model replicas on one device).  grads, residues and
+ * packets_out are HOST arrays of n_learners DEVICE pointers; residues and packets must be
+ * distinct buffers; every packet buffer has packet_capacity bytes.  Learner k's result is exactly
+ * what adacomp_compress gives for (grads[k], residues[k], packets_out[k]).  The workspace must
+ * have been initialised with at least adacomp_workspace_bytes_batch(layers, n_layers, n_learners)
+ * bytes.  Cites: every learner runs Algorithm 2 on its own gradient and residue (Algorithm 1,
+ * "pack()" precedes "exchange()"), so learners are independent until unpack. */
+int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                           const float *const *grads, float *const *residues, void *const *packets_out,
+                           size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---- unpack() of all learners, summed ("unpack()" then the sum inside "averageGradients()") -- */
 
 /* packets    HOST array of n_learners DEVICE pointers to complete packets made by
@@ -150,11 +167,15 @@ int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
 
 const char *adacomp_strerror(int code);
 
-/* Where adacomp_compress leaves the g_max vector (one float per bin, layers in table order, bins
- * in order) inside the workspace: byte offset and number of floats.  For tests of the first loop
- * of Algorithm 2. */
+/* The g_max vector (one float per bin, layers in table order, bins in order) is not needed once
+ * the layer scale is known, so compress does not store it unless adacomp_debug_keep_gmax(1) has
+ * been called.  adacomp_workspace_gmax says where it is then left inside the workspace: byte
+ * offset and number of floats for the first learner of a call, and (if not NULL) the distance in
+ * bytes to the next learner's vector in a batched call.  For tests of the first loop of
+ * Algorithm 2. */
+int adacomp_debug_keep_gmax(int enable);
 int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset,
-                           size_t *n_bins_total);
+                           size_t *n_bins_total, size_t *learner_stride);
 
 /* Plain float4 device copy of n floats (dst, src 16-byte aligned): the reference kernel against
  * which HBM byte counters and the achievable copy bandwidth are calibrated. */
@@ -164,8 +185,8 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
  * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
 int adacomp_selftest_binindex(void);
 
-/* Per-kernel timing of adacomp_compress's streaming kernel with HIP events on the caller's
- * stream.  enable != 0 starts recording (and clears earlier records); adacomp_timing_read
+/* Per-kernel timing of the streaming kernel of adacomp_compress / adacomp_compress_batch (one
+ * launch per call, covering all learners of the call) with HIP events on the caller's stream.  enable != 0 starts recording (and clears earlier records); adacomp_timing_read
  * synchronises the recorded events and returns their summed duration and count. */
 int adacomp_timing_enable(int enable);
 int adacomp_timing_read(double *total_ms, uint64_t *n_launches);

@@ -18,8 +18,10 @@ OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
-    "adacomp_workspace_init", "adacomp_workspace_release", "adacomp_compress",
-    "adacomp_unpack_accumulate", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_copy_f32",
+    "adacomp_workspace_bytes_batch", "adacomp_workspace_init", "adacomp_workspace_release",
+    "adacomp_compress", "adacomp_compress_batch",
+    "adacomp_unpack_accumulate", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
+    "adacomp_copy_f32",
     "adacomp_selftest_binindex", "adacomp_timing_enable", "adacomp_timing_read",
 ]
 
@@ -56,13 +58,18 @@ def lib():
         for name in ("adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [LP, u32]
+        L.adacomp_workspace_bytes_batch.restype = sz
+        L.adacomp_workspace_bytes_batch.argtypes = [LP, u32, u32]
+        L.adacomp_compress_batch.argtypes = [LP, u32, u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                             ctypes.POINTER(vp), sz, vp, sz, vp]
         L.adacomp_workspace_init.argtypes = [LP, u32, vp, sz, vp]
         L.adacomp_workspace_release.argtypes = [vp]
         L.adacomp_compress.argtypes = [LP, u32, vp, vp, vp, sz, vp, sz, vp]
         L.adacomp_unpack_accumulate.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, sz, vp]
         L.adacomp_strerror.restype = ctypes.c_char_p
         L.adacomp_strerror.argtypes = [ctypes.c_int]
-        L.adacomp_workspace_gmax.argtypes = [LP, u32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.adacomp_workspace_gmax.argtypes = [LP, u32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.adacomp_debug_keep_gmax.argtypes = [ctypes.c_int]
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
         L.adacomp_timing_enable.argtypes = [ctypes.c_int]
         L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
@@ -104,6 +111,10 @@ def adacomp_workspace_bytes(layers) -> int:
     return int(lib().adacomp_workspace_bytes(layer_array(layers), len(layers)))
 
 
+def adacomp_workspace_bytes_batch(layers, n_learners) -> int:
+    return int(lib().adacomp_workspace_bytes_batch(layer_array(layers), len(layers), int(n_learners)))
+
+
 def adacomp_workspace_init(layers, workspace):
     _check(lib().adacomp_workspace_init(layer_array(layers), len(layers), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
@@ -121,6 +132,18 @@ def adacomp_compress(layers, grad, residue, packet_out, workspace, packet_capaci
                                   workspace.numel() * workspace.element_size(), _stream()))
 
 
+def adacomp_compress_batch(layers, grads, residues, packets_out, workspace, packet_capacity=None):
+    """grads, residues: lists of float32 CUDA tensors; packets_out: list of uint8 CUDA tensors."""
+    n = len(grads)
+    cap = min(p.numel() for p in packets_out) if packet_capacity is None else int(packet_capacity)
+    vp = ctypes.c_void_p
+    g = (vp * n)(*[t.data_ptr() for t in grads])
+    r = (vp * n)(*[t.data_ptr() for t in residues])
+    p = (vp * n)(*[t.data_ptr() for t in packets_out])
+    _check(lib().adacomp_compress_batch(layer_array(layers), len(layers), n, g, r, p, cap, _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+
+
 def adacomp_unpack_accumulate(layers, packets, dense_out, workspace):
     """packets: list of uint8 CUDA tensors (one per learner)."""
     ptrs = (ctypes.c_void_p * max(1, len(packets)))(*[p.data_ptr() for p in packets])
@@ -130,9 +153,14 @@ def adacomp_unpack_accumulate(layers, packets, dense_out, workspace):
 
 
 def adacomp_workspace_gmax(layers):
-    off, n = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().adacomp_workspace_gmax(layer_array(layers), len(layers), ctypes.byref(off), ctypes.byref(n)))
-    return off.value, n.value
+    off, n, stride = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().adacomp_workspace_gmax(layer_array(layers), len(layers), ctypes.byref(off), ctypes.byref(n),
+                                        ctypes.byref(stride)))
+    return off.value, n.value, stride.value
+
+
+def adacomp_debug_keep_gmax(on: bool):
+    _check(lib().adacomp_debug_keep_gmax(1 if on else 0))
 
 
 def adacomp_copy_f32(dst, src, n=None):

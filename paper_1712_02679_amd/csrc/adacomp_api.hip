@@ -30,7 +30,7 @@ int default_register_class()
     static int cls = [] {
         const char *e = std::getenv("ADACOMP_TILE_CLASS");
         int v = e ? std::atoi(e) : 0;
-        return v < 0 ? 0 : (v > 2 ? 2 : v);
+        return v < -1 ? -1 : (v > 2 ? 2 : v);   // -1: tiles of 2048 elements
     }();
     return cls;
 }
@@ -41,7 +41,7 @@ uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers)
     auto mix = [&h](uint64_t v) { for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xFF; h *= 1099511628211ull; } };
     mix(n_layers);
     for (uint32_t l = 0; l < n_layers; ++l) { mix(layers[l].elem_offset); mix(layers[l].n_elems); mix(layers[l].L_T); }
-    mix(uint64_t(default_register_class()));
+    mix(uint64_t(int64_t(default_register_class())));
     return h;
 }
 
@@ -108,10 +108,12 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         p.n_elems_total += n;
 
         // ---- compress tiles: whole bins, as many as fit the register class --------------------
+        // Tiles of 8192 elements (class 1) stream at less than half the rate of 4096 or 16384 on
+        // MI355X (measured on a plain triad), so bins above 4096 go straight to class 2.
         int cls = base_cls;
-        if (T > 4096u && cls < 1) cls = 1;
-        if (T > 8192u) cls = 2;
-        const uint32_t cap = 4096u << cls;
+        if (cls < 0 && T > 2048u) cls = 0;
+        if (cls >= 0 && T > (4096u << cls)) cls = 2;
+        const uint32_t cap = cls < 0 ? 2048u : 4096u << cls;
         uint32_t bpt = cap / T;                       // >= 1
         if (bpt > kMaxTileBins) bpt = kMaxTileBins;
         const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
@@ -119,7 +121,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         const uint32_t nt = (n_bins + bpt - 1) / bpt;
         ld.ctile_start = uint32_t(n_ctiles);
         ld.n_ctiles = nt;
-        p.has_class[cls] = true;
+        p.has_class[cls < 0 ? 3 : cls] = true;
         if (tables) {
             for (uint32_t t = 0; t < nt; ++t) {
                 TileDev td;
@@ -131,7 +133,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
                 td.magic = bin_magic(T);
                 td.n_bins = (td.n_elems + T - 1) / T;
                 td.first_bin = first_bin;
-                td.layer_flags = l | (uint32_t(cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
+                td.layer_flags = l | (uint32_t(cls < 0 ? 3 : cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
                 p.ctiles.push_back(td);
             }
         }
@@ -188,32 +190,33 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     p.n_chunks_total = uint32_t(chunks_total);
     p.fixed_bytes = fixed;
     p.bound_bytes = fixed + words_bound;
+    if (p.bound_bytes >= (uint64_t(1) << 32)) return ADACOMP_EINVAL;  // word positions are 32-bit in k_unpack
 
     WorkspaceLayout &w = p.ws;
     size_t off = 256;  // first 256 bytes: reserved
     w.layers = off;      off = pad256(off + sizeof(LayerDev) * size_t(n_layers));
     w.ctiles = off;      off = pad256(off + sizeof(TileDev) * size_t(p.n_ctiles));
     w.utiles = off;      off = pad256(off + sizeof(UTileDev) * size_t(p.n_utiles));
-    w.tile_count = off;  off = pad256(off + 4 * size_t(p.n_ctiles));
-    w.tile_base = off;   off = pad256(off + 4 * size_t(p.n_ctiles));
-    w.tile_sum = off;    off = pad256(off + 8 * size_t(p.n_ctiles));
+    w.scratch = off;
+    off = 0;             // offsets inside one learner's scratch block
+    w.tile_out = off;    off = pad256(off + sizeof(TileOut) * size_t(p.n_ctiles));
     w.layer_nsel = off;  off = pad256(off + 4 * size_t(n_layers));
     w.layer_scale = off; off = pad256(off + 4 * size_t(n_layers));
     w.gmax = off;        off = pad256(off + 4 * size_t(p.n_bins_total));
     w.chunk_rel = off;   off = pad256(off + 4 * size_t(p.n_chunks_total));
+    if (off >= (size_t(1) << 32)) return ADACOMP_EINVAL;
     w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span) + 64);  // slack: k_place reads 16 entries ahead
-    w.stage_g = off;     off = pad256(off + 4 * size_t(p.elem_span) + 64);
-    w.total = off;
+    w.scratch_stride = off;
     return ADACOMP_OK;
 }
 
 // Workspaces that adacomp_workspace_init has filled, by address.
-struct Registered { Plan plan; };
+struct Registered { Plan plan; size_t bytes = 0; };
 static std::mutex g_mu;
 static std::unordered_map<const void *, Registered> g_ws;
 
 static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace,
-                     size_t workspace_bytes, Plan &out)
+                     size_t workspace_bytes, size_t n_learners, Plan &out)
 {
     if (!layers || n_layers == 0 || !workspace) return ADACOMP_EINVAL;
     std::lock_guard<std::mutex> lk(g_mu);
@@ -221,13 +224,13 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     if (it == g_ws.end()) return ADACOMP_EWORKSPACE;
     const Plan &p = it->second.plan;
     if (p.n_layers != n_layers || p.table_hash != hash_table(layers, n_layers)) return ADACOMP_EWORKSPACE;
-    if (workspace_bytes < p.ws.total) return ADACOMP_EWORKSPACE;
+    if (workspace_bytes < p.ws.total(n_learners) || it->second.bytes < p.ws.total(n_learners)) return ADACOMP_EWORKSPACE;
     // copy the scalars only; the tables already live on the device
     out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles;
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
-    for (int c = 0; c < 3; ++c) out.has_class[c] = p.has_class[c];
+    for (int c = 0; c < 4; ++c) out.has_class[c] = p.has_class[c];
     out.table_hash = p.table_hash; out.ws = p.ws;
     return ADACOMP_OK;
 }
@@ -239,6 +242,7 @@ struct Timing {
     size_t used = 0;
 };
 static Timing g_timing;
+static bool g_keep_gmax = false;
 
 }  // namespace adacomp
 
@@ -261,17 +265,26 @@ size_t adacomp_packet_fixed_bytes(const adacomp_layer_t *layers, uint32_t n_laye
 size_t adacomp_workspace_bytes(const adacomp_layer_t *layers, uint32_t n_layers)
 {
     Plan p;
-    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? p.ws.total : 0;
+    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? p.ws.total(1) : 0;
 }
 
-int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset, size_t *n_bins_total)
+size_t adacomp_workspace_bytes_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners)
+{
+    Plan p;
+    if (n_learners == 0) return 0;
+    return build_plan(layers, n_layers, false, p) == ADACOMP_OK ? p.ws.total(n_learners) : 0;
+}
+
+int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset,
+                           size_t *n_bins_total, size_t *learner_stride)
 {
     if (!byte_offset || !n_bins_total) return ADACOMP_EINVAL;
     Plan p;
     int rc = build_plan(layers, n_layers, false, p);
     if (rc != ADACOMP_OK) return rc;
-    *byte_offset = p.ws.gmax;
+    *byte_offset = p.ws.scratch + p.ws.gmax;
     *n_bins_total = p.n_bins_total;
+    if (learner_stride) *learner_stride = p.ws.scratch_stride;
     return ADACOMP_OK;
 }
 
@@ -284,7 +297,7 @@ int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, voi
     int rc = build_plan(layers, n_layers, true, reg.plan);
     if (rc != ADACOMP_OK) return rc;
     Plan &p = reg.plan;
-    if (workspace_bytes < p.ws.total) return ADACOMP_EWORKSPACE;
+    if (workspace_bytes < p.ws.total(1)) return ADACOMP_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (hipStreamSynchronize(s) != hipSuccess) return ADACOMP_EHIP;
     char *ws = static_cast<char *>(workspace);
@@ -296,6 +309,7 @@ int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, voi
     p.ctiles.clear(); p.ctiles.shrink_to_fit();
     p.utiles.clear(); p.utiles.shrink_to_fit();
     std::lock_guard<std::mutex> lk(g_mu);
+    reg.bytes = workspace_bytes;
     g_ws[workspace] = std::move(reg);
     return ADACOMP_OK;
 }
@@ -306,16 +320,21 @@ int adacomp_workspace_release(void *workspace)
     return g_ws.erase(workspace) ? ADACOMP_OK : ADACOMP_EINVAL;
 }
 
-int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
-                     float *residue, void *packet_out, size_t packet_capacity, void *workspace,
-                     size_t workspace_bytes, void *hip_stream)
+int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                           const float *const *grads, float *const *residues, void *const *packets_out,
+                           size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!grad || !residue || !packet_out || grad == residue) return ADACOMP_EINVAL;
-    if (reinterpret_cast<uintptr_t>(grad) % 16 || reinterpret_cast<uintptr_t>(residue) % 16 ||
-        reinterpret_cast<uintptr_t>(packet_out) % 16)
-        return ADACOMP_EALIGN;
+    if (n_learners == 0 || !grads || !residues || !packets_out) return ADACOMP_EINVAL;
+    for (uint32_t k = 0; k < n_learners; ++k) {
+        if (!grads[k] || !residues[k] || !packets_out[k] || grads[k] == residues[k]) return ADACOMP_EINVAL;
+        if (reinterpret_cast<uintptr_t>(grads[k]) % 16 || reinterpret_cast<uintptr_t>(residues[k]) % 16 ||
+            reinterpret_cast<uintptr_t>(packets_out[k]) % 16)
+            return ADACOMP_EALIGN;
+        for (uint32_t m = 0; m < k; ++m)
+            if (residues[k] == residues[m] || packets_out[k] == packets_out[m]) return ADACOMP_EINVAL;
+    }
     Plan p;
-    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, p);
+    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, n_learners, p);
     if (rc != ADACOMP_OK) return rc;
     if (packet_capacity < p.fixed_bytes) return ADACOMP_ENOSPC;
 
@@ -323,39 +342,56 @@ int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const flo
     CompressArgs a;
     a.tiles = reinterpret_cast<const TileDev *>(ws + p.ws.ctiles);
     a.layers = reinterpret_cast<const LayerDev *>(ws + p.ws.layers);
-    a.grad = grad;
-    a.residue = residue;
-    a.packet = static_cast<uint8_t *>(packet_out);
-    a.capacity = packet_capacity;
-    a.tile_count = reinterpret_cast<uint32_t *>(ws + p.ws.tile_count);
-    a.tile_base = reinterpret_cast<uint32_t *>(ws + p.ws.tile_base);
-    a.tile_sum = reinterpret_cast<double *>(ws + p.ws.tile_sum);
-    a.layer_nsel = reinterpret_cast<uint32_t *>(ws + p.ws.layer_nsel);
-    a.layer_scale = reinterpret_cast<float *>(ws + p.ws.layer_scale);
-    a.gmax = reinterpret_cast<float *>(ws + p.ws.gmax);
-    a.chunk_rel = reinterpret_cast<uint32_t *>(ws + p.ws.chunk_rel);
-    a.stage = reinterpret_cast<uint16_t *>(ws + p.ws.stage);
-    a.stage_g = reinterpret_cast<uint32_t *>(ws + p.ws.stage_g);
+    a.scratch_stride = p.ws.scratch_stride;
+    a.o_tile_out = uint32_t(p.ws.tile_out); a.o_layer_nsel = uint32_t(p.ws.layer_nsel);
+    a.o_layer_scale = uint32_t(p.ws.layer_scale); a.o_gmax = uint32_t(p.ws.gmax);
+    a.o_chunk_rel = uint32_t(p.ws.chunk_rel); a.o_stage = p.ws.stage;
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
+    a.keep_gmax = g_keep_gmax ? 1u : 0u;
+    a.capacity = packet_capacity;
     a.fixed_bytes = p.fixed_bytes;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
-    if (g_timing.on) {
-        if (g_timing.used == g_timing.pool.size()) {
-            hipEvent_t e0, e1;
-            if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
-            g_timing.pool.emplace_back(e0, e1);
+    static const uint32_t chunk = [] {
+        const char *e = std::getenv("ADACOMP_BATCH_CHUNK");
+        const int v = e ? std::atoi(e) : int(kMaxBatch);
+        return uint32_t(v < 1 ? 1 : (v > int(kMaxBatch) ? int(kMaxBatch) : v));
+    }();
+    for (uint32_t done = 0; done < n_learners; done += chunk) {
+        const uint32_t now = std::min(n_learners - done, chunk);
+        a.n_learners = now;
+        a.scratch = reinterpret_cast<uint8_t *>(ws + p.ws.scratch + p.ws.scratch_stride * done);
+        for (uint32_t k = 0; k < kMaxBatch; ++k) {
+            a.grad[k] = k < now ? grads[done + k] : nullptr;
+            a.residue[k] = k < now ? residues[done + k] : nullptr;
+            a.packet[k] = k < now ? static_cast<uint8_t *>(packets_out[done + k]) : nullptr;
         }
-        ev = &g_timing.pool[g_timing.used++];
-        if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
+        std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
+        if (g_timing.on) {
+            if (g_timing.used == g_timing.pool.size()) {
+                hipEvent_t e0, e1;
+                if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
+                g_timing.pool.emplace_back(e0, e1);
+            }
+            ev = &g_timing.pool[g_timing.used++];
+            if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
+        }
+        for (int c = 0; c < 4; ++c)
+            if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
+        if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
+        if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
+        if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
-    for (int c = 0; c < 3; ++c)
-        if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
-    if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
-    if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
-    return launch_place(a, hip_stream);
+    return ADACOMP_OK;
+}
+
+int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
+                     float *residue, void *packet_out, size_t packet_capacity, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    return adacomp_compress_batch(layers, n_layers, 1, &grad, &residue, &packet_out, packet_capacity,
+                                  workspace, workspace_bytes, hip_stream);
 }
 
 int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
@@ -369,7 +405,7 @@ int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
         if (reinterpret_cast<uintptr_t>(packets[k]) % 16) return ADACOMP_EALIGN;
     }
     Plan p;
-    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, p);
+    int rc = find_plan(layers, n_layers, workspace, workspace_bytes, 1, p);
     if (rc != ADACOMP_OK) return rc;
 
     char *ws = static_cast<char *>(workspace);
@@ -424,6 +460,12 @@ int adacomp_selftest_binindex(void)
         }
     }
     return 0;
+}
+
+int adacomp_debug_keep_gmax(int enable)
+{
+    g_keep_gmax = enable != 0;
+    return ADACOMP_OK;
 }
 
 int adacomp_timing_enable(int enable)

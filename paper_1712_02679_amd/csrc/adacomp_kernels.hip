@@ -21,6 +21,9 @@
 // tile is written out once with coalesced float4 stores.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <type_traits>
+
 #include "adacomp_plan.h"
 
 namespace adacomp {
@@ -84,10 +87,22 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 template <int J>
 __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 {
-    const uint32_t tile = blockIdx.x;
-    if (tile >= a.n_tiles) return;
+    // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
+    // call streams one learner's buffers after the other instead of all of them at once
+    const uint32_t lr = blockIdx.x / a.n_tiles;
+    const uint32_t tile = blockIdx.x - lr * a.n_tiles;
     const TileDev td = a.tiles[tile];
-    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
+    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : (J == 16 ? 2u : 3u)))) return;
+    uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
+    TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
+    uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
+    float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
+    float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
+    uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
+    uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
+    uint8_t *const packet = a.packet[lr];
+    (void)tile_out; (void)layer_nsel; (void)layer_scale;
+    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
 
     __shared__ uint32_t s_gmax[kMaxTileBins];  // bit pattern of max |G|: for non-negative floats the
     __shared__ uint32_t s_cnt[kMaxTileBins];   // unsigned integer order is the float order
@@ -101,8 +116,8 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 
     for (uint32_t i = tid; i < nb; i += kWG) { s_gmax[i] = 0u; s_cnt[i] = 0u; }
 
-    const float *__restrict__ gr = a.grad + td.elem_base;
-    float *__restrict__ rs = a.residue + td.elem_base;
+    const float *__restrict__ gr = a.grad[lr] + td.elem_base;
+    float *__restrict__ rs = a.residue[lr] + td.elem_base;
 
     // ---- G <- residue + dW ; H <- G + dW ; residue <- G (the "no transmission" value) ----------
     float r[J][4], w[J][4];
@@ -207,8 +222,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     const uint32_t tile_total = __shfl(row_incl, 4 * J - 1, 64);
 
     // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
-    uint16_t *__restrict__ stage = a.stage + td.elem_base;
-    uint32_t *__restrict__ stage_g = a.stage_g + td.elem_base;  // G of the sent elements, for k_place
+    uint16_t *__restrict__ stage = stage_all + td.elem_base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
@@ -221,7 +235,6 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
                     const uint32_t e = e0 + uint32_t(c);
                     const uint32_t code = (gb[j][c] >> 31) ? 3u : 1u;  // ternary value: -scale / +scale
                     stage[pos] = uint16_t((e << 2) | code);
-                    stage_g[pos] = gb[j][c];
                     ++pos;
                     atomicAdd(&s_cnt[bin_of(e, T, M)], 1u);
                 }
@@ -233,17 +246,17 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     // ---- tile outputs: counts (into the packet), g_max, sum of g_max, chunk prefixes, total ----
     const LayerDev ld = a.layers[td.layer()];
     if (ld.word_bytes == 1u) {
-        uint8_t *cp = a.packet + ld.counts_offset + td.first_bin;
+        uint8_t *cp = packet + ld.counts_offset + td.first_bin;
         for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint8_t(s_cnt[i]);
     } else {
-        uint16_t *cp = reinterpret_cast<uint16_t *>(a.packet + ld.counts_offset) + td.first_bin;
+        uint16_t *cp = reinterpret_cast<uint16_t *>(packet + ld.counts_offset) + td.first_bin;
         for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint16_t(s_cnt[i]);
     }
     double part = 0.0;
-    float *gm_out = a.gmax + ld.bin_start + td.first_bin;
+    float *gm_out = gmax_out + ld.bin_start + td.first_bin;
     for (uint32_t i = tid; i < nb; i += kWG) {
         const float g = __uint_as_float(s_gmax[i]);
-        gm_out[i] = g;
+        if (a.keep_gmax) gm_out[i] = g;  // diagnostics only: no later kernel reads the g_max vector
         part += double(g);
     }
     part = wave_sum_f64(part);
@@ -254,12 +267,15 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
         uint32_t sum = 0u;
         for (uint32_t i = lane; i < t; i += 64u) sum += s_cnt[i];
         sum = wave_sum(sum);
-        if (lane == 0) a.chunk_rel[ld.chunk_start + ((td.first_bin + t) >> 6)] = sum;
+        if (lane == 0) chunk_rel[ld.chunk_start + ((td.first_bin + t) >> 6)] = sum;
     }
     __syncthreads();
     if (tid == 0) {
-        a.tile_sum[tile] = ((s_red[0] + s_red[1]) + s_red[2]) + s_red[3];
-        a.tile_count[tile] = tile_total;
+        TileOut o;
+        o.gmax_sum = ((s_red[0] + s_red[1]) + s_red[2]) + s_red[3];
+        o.count = tile_total;
+        o.base = 0u;  // filled in by k_scan
+        tile_out[tile] = o;  // one 16-byte store
     }
 }
 
@@ -274,6 +290,18 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
 {
     const uint32_t l = blockIdx.x;
     if (l >= a.n_layers) return;
+    // per-learner buffers: blockIdx.y selects the learner of a batched call
+    const uint32_t lr = blockIdx.y;
+    uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
+    TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
+    uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
+    float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
+    float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
+    uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
+    uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
+    uint8_t *const packet = a.packet[lr];
+    (void)tile_out; (void)layer_nsel; (void)layer_scale;
+    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
     const LayerDev ld = a.layers[l];
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
@@ -288,7 +316,7 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
     uint32_t csum = 0u;
     double dsum = 0.0;
 #pragma unroll 8
-    for (uint32_t i = lo; i < hi; ++i) { csum += a.tile_count[ts + i]; dsum += a.tile_sum[ts + i]; }
+    for (uint32_t i = lo; i < hi; ++i) { const TileOut o = tile_out[ts + i]; csum += o.count; dsum += o.gmax_sum; }
 
     const uint32_t incl = wave_incl_scan(csum, lane);
     dsum = wave_sum_f64(dsum);
@@ -299,13 +327,13 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
     for (uint32_t wv = 0; wv < wave; ++wv) wave_base += s_wsum[wv];
     uint32_t run = wave_base + incl - csum;
 #pragma unroll 8
-    for (uint32_t i = lo; i < hi; ++i) { a.tile_base[ts + i] = run; run += a.tile_count[ts + i]; }
+    for (uint32_t i = lo; i < hi; ++i) { tile_out[ts + i].base = run; run += tile_out[ts + i].count; }
     if (tid == 0) {
         double total = 0.0;
         uint32_t nsel = 0u;
         for (uint32_t wv = 0; wv < kScanWG / 64u; ++wv) { total += s_dsum[wv]; nsel += s_wsum[wv]; }
-        a.layer_scale[l] = float(total / double(ld.n_bins));
-        a.layer_nsel[l] = nsel;
+        layer_scale[l] = float(total / double(ld.n_bins));
+        layer_nsel[l] = nsel;
     }
 }
 
@@ -322,6 +350,18 @@ constexpr uint32_t kPlaceTiles = kWG / kPlaceLanes;
 __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 {
     const uint32_t tid = threadIdx.x;
+    // per-learner buffers: blockIdx.y selects the learner of a batched call
+    const uint32_t lr = blockIdx.y;
+    uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
+    TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
+    uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
+    float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
+    float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
+    uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
+    uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
+    uint8_t *const packet = a.packet[lr];
+    (void)tile_out; (void)layer_nsel; (void)layer_scale;
+    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
 
     if (blockIdx.x == gridDim.x - 1) {
         // ---- header, layer records, zero padding ------------------------------------------------
@@ -331,21 +371,21 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
         for (uint32_t l = tid; l < a.n_layers; l += kWG) {
             const LayerDev ld = a.layers[l];
             uint64_t woff = a.fixed_bytes;
-            for (uint32_t m = 0; m < l; ++m) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
-            const uint64_t nsel = a.layer_nsel[l];
+            for (uint32_t m = 0; m < l; ++m) woff += pad16_dev(uint64_t(layer_nsel[m]) * a.layers[m].word_bytes);
+            const uint64_t nsel = layer_nsel[l];
             adacomp_packet_layer_t rec;
             rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
             rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
-            rec.scale = a.layer_scale[l];
+            rec.scale = layer_scale[l];
             rec.n_selected = nsel;
             rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
-            reinterpret_cast<adacomp_packet_layer_t *>(a.packet + sizeof(adacomp_packet_header_t))[l] = rec;
-            for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) a.packet[b] = 0;
+            reinterpret_cast<adacomp_packet_layer_t *>(packet + sizeof(adacomp_packet_header_t))[l] = rec;
+            for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) packet[b] = 0;
             const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
-            for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) a.packet[b] = 0;
+            for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) packet[b] = 0;
             const uint64_t words_end = woff + nsel * ld.word_bytes;
             for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
-                if (b < a.capacity) a.packet[b] = 0;
+                if (b < a.capacity) packet[b] = 0;
             if (l == a.n_layers - 1) s_total = pad16_dev(words_end);
             atomicAdd(reinterpret_cast<unsigned long long *>(&s_nsel), (unsigned long long)nsel);
         }
@@ -355,7 +395,7 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
             h.magic = ADACOMP_PACKET_MAGIC; h.version = ADACOMP_PACKET_VERSION;
             h.status = s_total > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
             h.n_layers = a.n_layers; h.total_bytes = s_total; h.n_selected = s_nsel;
-            *reinterpret_cast<adacomp_packet_header_t *>(a.packet) = h;
+            *reinterpret_cast<adacomp_packet_header_t *>(packet) = h;
         }
         return;
     }
@@ -367,20 +407,19 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     const uint32_t l = td.layer();
 
     // independent loads first: the tile's counters, its first staged entries, the layer's fields
-    const uint32_t cnt = a.tile_count[tile], base = a.tile_base[tile];
-    const uint16_t *__restrict__ stage = a.stage + td.elem_base;
-    float *__restrict__ rs = a.residue + td.elem_base;
-    const uint32_t *__restrict__ stage_g = a.stage_g + td.elem_base;
-    const uint32_t s_first = stage[sub];  // speculative: the staging arrays have 16 entries of slack
-    const uint32_t g_first = stage_g[sub];
-    const float scale = a.layer_scale[l];
+    const TileOut to = tile_out[tile];
+    const uint32_t cnt = to.count, base = to.base;
+    const uint16_t *__restrict__ stage = stage_all + td.elem_base;
+    float *__restrict__ rs = a.residue[lr] + td.elem_base;
+    const uint32_t s_first = stage[sub];  // speculative: the staging array has 16 entries of slack
+    const float scale = layer_scale[l];
     const uint32_t wbytes = a.layers[l].word_bytes;
     const uint64_t chunks_offset = a.layers[l].chunks_offset;
     const uint32_t chunk_start = a.layers[l].chunk_start;
 
     // first word of this layer = end of the fixed part + the (padded) word sections before it
     uint64_t woff = 0;
-    for (uint32_t m = sub; m < l; m += kPlaceLanes) woff += pad16_dev(uint64_t(a.layer_nsel[m]) * a.layers[m].word_bytes);
+    for (uint32_t m = sub; m < l; m += kPlaceLanes) woff += pad16_dev(uint64_t(layer_nsel[m]) * a.layers[m].word_bytes);
 #pragma unroll
     for (uint32_t d = kPlaceLanes / 2; d > 0; d >>= 1) {
         const uint32_t lo = __shfl_xor(uint32_t(woff), d, kPlaceLanes), hi = __shfl_xor(uint32_t(woff >> 32), d, kPlaceLanes);
@@ -391,17 +430,18 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     const uint32_t T = td.L_T, M = td.magic;
     for (uint32_t p = sub; p < cnt; p += kPlaceLanes) {
         const uint32_t s = p == sub ? s_first : uint32_t(stage[p]);
-        const float g = __uint_as_float(p == sub ? g_first : stage_g[p]);
         const uint32_t e = s >> 2, code = s & 3u;
         const uint32_t b = bin_of(e, T, M);
         const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
         const uint64_t at = woff + uint64_t(base + p) * wbytes;
         if (at + wbytes <= a.capacity) {
-            if (wbytes == 1u) a.packet[at] = uint8_t(word);
-            else *reinterpret_cast<uint16_t *>(a.packet + at) = uint16_t(word);
+            if (wbytes == 1u) packet[at] = uint8_t(word);
+            else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
         }
-        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale.  G comes from the staging
-        // area, so this is a 4-byte store and the residue line is not read back
+        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left there.
+        // (Staging G next to the word, to turn this read-modify-write into a plain store, was
+        // measured: it takes as much from k_fused as it saves here.)
+        const float g = rs[e];
         rs[e] = code == 1u ? g - scale : g + scale;
     }
 
@@ -409,36 +449,163 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
     for (uint32_t t = t0 + 64u * sub; t < td.n_bins; t += 64u * kPlaceLanes) {
         const uint32_t c = (td.first_bin + t) >> 6;
-        reinterpret_cast<uint32_t *>(a.packet + chunks_offset)[c] = base + a.chunk_rel[chunk_start + c];
+        reinterpret_cast<uint32_t *>(packet + chunks_offset)[c] = base + chunk_rel[chunk_start + c];
     }
 }
 
 // ==============================================================================================
 // k_unpack: dense_out <- sum over learners, in learner order, of the decoded packets.
 // A workgroup owns a tile of the output in LDS.  Per group of 16 learners it first gathers, for
-// every (learner, bin) of the tile, where the bin's words start (all learners' loads in flight
-// together), then a lane group per bin fetches the words of all 16 learners before adding them in
-// learner order.  The adds to one LDS address come from one wave in program order, so the sum
-// order is fixed without atomics.
+// every (bin, learner) of the tile, the word count and the position of the first word (one wave
+// per learner, all learners' loads in flight together), then a lane group per bin reads the 16
+// learners' table entries with a few wide LDS loads, fetches the words of all 16 learners, and
+// adds +-scale with LDS float atomics in learner order.  All adds to one address come from one
+// wave in program order and the LDS unit executes a wave's operations in order, so the sum
+// order is fixed: learner 0 first.  (LDS float adds round to nearest even and keep denormals,
+// like v_add_f32.)
 // ==============================================================================================
+template <bool W8>
+__device__ __forceinline__ void unpack_tile(const UnpackArgs &a, const UTileDev &ut, const LayerDev &ld,
+                                            float *s_acc, uint32_t (*s_off)[kLearnerGroup],
+                                            uint16_t (*s_cnt)[kLearnerGroup], float *s_scale, uint32_t *s_cmax)
+{
+    typedef typename std::conditional<W8, uint8_t, uint16_t>::type word_t;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
+    const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
+    const uint32_t chunk = ut.first_bin >> 6;
+    const uint32_t b = (chunk << 6) + lane;           // the bin this lane looks up in phase 1
+    const bool in_scan = b < ut.first_bin + nb;       // bins of the chunk up to the end of the tile
+    const bool in_tile = in_scan && b >= ut.first_bin;
+    constexpr uint32_t kPerWave = kLearnerGroup / 4u;
+
+    for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
+        const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
+        __syncthreads();  // accumulators initialised / previous group finished with the tables
+        if (tid == 0) *s_cmax = 0u;
+        __syncthreads();
+
+        // ---- phase 1: wave w serves learners w, w + 4, ...; all their loads are issued first ----
+        uint32_t c[kPerWave], coff[kPerWave], wbase[kPerWave];
+        float sc[kPerWave];
+        bool ok[kPerWave];
+#pragma unroll
+        for (uint32_t q = 0; q < kPerWave; ++q) {
+            const uint32_t kk = wave + 4u * q;
+            c[q] = 0u; coff[q] = 0u; wbase[q] = 0u; sc[q] = 0.f; ok[q] = false;
+            if (kk < nk) {
+                const uint8_t *pk = a.packets[k0 + kk];
+                const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers
+                ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
+                        (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
+                // counts and chunk offsets sit in the fixed part, which every packet buffer holds
+                if (in_scan) c[q] = reinterpret_cast<const word_t *>(pk + ld.counts_offset)[b];
+                coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
+                const adacomp_packet_layer_t *rec =
+                    reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
+                sc[q] = rec->scale;
+                wbase[q] = uint32_t(rec->words_offset / sizeof(word_t));  // packets stay below 2^32 words (host check)
+            }
+        }
+        uint32_t wmax = 0u;
+#pragma unroll
+        for (uint32_t q = 0; q < kPerWave; ++q) {
+            const uint32_t kk = wave + 4u * q;  // < kLearnerGroup; learners past nk get empty entries
+            const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
+            const uint32_t incl = wave_incl_scan(cq, lane);
+            if (in_tile) {
+                s_off[b - ut.first_bin][kk] = wbase[q] + coff[q] + incl - cq;
+                s_cnt[b - ut.first_bin][kk] = uint16_t(cq);
+            }
+            if (lane == 0) s_scale[kk] = sc[q];
+            wmax = (in_tile && cq > wmax) ? cq : wmax;
+        }
+#pragma unroll
+        for (uint32_t d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(wmax, d, 64); wmax = o > wmax ? o : wmax; }
+        if (lane == 0) atomicMax(s_cmax, wmax);
+        __syncthreads();
+        // lanes per bin: the smallest power of two that holds the tile's largest word count, between
+        // the table's default (8 or 16) and the whole wave
+        uint32_t glog = ut.group_log2();
+        while (glog < 6u && (1u << glog) < *s_cmax) ++glog;
+        const uint32_t gsz = 1u << glog;
+
+        // ---- phase 2: a lane group owns a bin --------------------------------------------------
+        float scl[kLearnerGroup];
+#pragma unroll
+        for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
+            const float4 t = *reinterpret_cast<const float4 *>(&s_scale[4u * v]);
+            scl[4 * v] = t.x; scl[4 * v + 1] = t.y; scl[4 * v + 2] = t.z; scl[4 * v + 3] = t.w;
+        }
+        for (uint32_t s = tid; s < (nb << glog); s += kWG) {
+            const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
+            const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
+            float *acc = s_acc + lb * T;
+            uint32_t cc[kLearnerGroup], off[kLearnerGroup];
+#pragma unroll
+            for (uint32_t v = 0; v < kLearnerGroup / 8u; ++v) {
+                const uint4 t = *reinterpret_cast<const uint4 *>(&s_cnt[lb][8u * v]);
+                cc[8 * v] = t.x & 0xFFFFu; cc[8 * v + 1] = t.x >> 16; cc[8 * v + 2] = t.y & 0xFFFFu; cc[8 * v + 3] = t.y >> 16;
+                cc[8 * v + 4] = t.z & 0xFFFFu; cc[8 * v + 5] = t.z >> 16; cc[8 * v + 6] = t.w & 0xFFFFu; cc[8 * v + 7] = t.w >> 16;
+            }
+#pragma unroll
+            for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
+                const uint4 t = *reinterpret_cast<const uint4 *>(&s_off[lb][4u * v]);
+                off[4 * v] = t.x; off[4 * v + 1] = t.y; off[4 * v + 2] = t.z; off[4 * v + 3] = t.w;
+            }
+            uint32_t word[kLearnerGroup];
+            uint32_t cmax = 0u;
+#pragma unroll
+            for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
+                cmax = cc[kk] > cmax ? cc[kk] : cmax;
+                word[kk] = 0u;
+                if (sub < cc[kk]) {
+                    const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + (kk < nk ? kk : 0u)]);
+                    word[kk] = wp[off[kk] + sub];
+                }
+            }
+            if (cmax <= gsz) {
+#pragma unroll
+                for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
+                    const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
+                    const uint32_t code = word[kk] & 3u;
+                    if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? scl[kk] : -scl[kk]);
+                }
+            } else {
+                // some learner sends more words from this bin than the group has lanes: plain loops,
+                // one learner after the other (same order)
+                for (uint32_t kk = 0; kk < nk; ++kk) {
+                    const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + kk]);
+                    const uint32_t cck = s_cnt[lb][kk], st = s_off[lb][kk];
+                    const float sck = s_scale[kk];
+                    for (uint32_t jw = sub; jw < cck; jw += gsz) {
+                        const uint32_t wd = wp[st + jw];
+                        const uint32_t idx = (wd >> 2) - ut.idx_lo;
+                        const uint32_t code = wd & 3u;
+                        if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
+                    }
+                }
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 {
     const uint32_t tile = blockIdx.x;
     if (tile >= a.n_tiles) return;
     const UTileDev ut = a.tiles[tile];
     const LayerDev ld = a.layers[ut.layer()];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
-    const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n = ut.n_elems;
     const bool vec = ut.aligned();
-    const bool w8 = ld.word_bytes == 1u;
     float *__restrict__ out = a.dense + ut.elem_base;
 
     __shared__ float s_acc[kUnpackTileElems];
-    __shared__ uint32_t s_start[kLearnerGroup][64];  // first word of (learner, bin) inside the layer's words
-    __shared__ uint16_t s_cnt[kLearnerGroup][64];
-    __shared__ float s_scale[kLearnerGroup];
-    __shared__ uint64_t s_words[kLearnerGroup];      // address of the layer's first word
+    __shared__ __attribute__((aligned(16))) uint32_t s_off[64][kLearnerGroup];  // first word of (bin, learner), counted from the packet start
+    __shared__ __attribute__((aligned(16))) uint16_t s_cnt[64][kLearnerGroup];
+    __shared__ __attribute__((aligned(16))) float s_scale[kLearnerGroup];
+    __shared__ uint32_t s_cmax;                                                // largest word count of a (bin, learner) in the tile
 
     // ---- tile accumulators: zero, or the partial sum of an earlier launch ----------------------
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
@@ -455,99 +622,8 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
         *reinterpret_cast<float4 *>(&s_acc[i]) = v;  // s_acc has room for the rounded-up tail
     }
 
-    const uint32_t chunk = ut.first_bin >> 6;
-    const uint32_t b = (chunk << 6) + lane;           // the bin this lane looks up in phase 1
-    const bool in_scan = b < ut.first_bin + nb;       // bins of the chunk up to the end of the tile
-    const bool in_tile = in_scan && b >= ut.first_bin;
-    const uint32_t glog = ut.group_log2(), gsz = 1u << glog;
-    constexpr uint32_t kPerWave = kLearnerGroup / 4u;
-
-    for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
-        const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
-        __syncthreads();  // accumulators initialised / previous group finished with the tables
-
-        // ---- phase 1: wave w serves learners w, w + 4, ...; all their loads are issued first ----
-        uint32_t c[kPerWave], coff[kPerWave];
-        bool ok[kPerWave];
-#pragma unroll
-        for (uint32_t q = 0; q < kPerWave; ++q) {
-            const uint32_t kk = wave + 4u * q;
-            c[q] = 0u; coff[q] = 0u; ok[q] = false;
-            if (kk < nk) {
-                const uint8_t *pk = a.packets[k0 + kk];
-                const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers in one load
-                ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
-                        (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
-                // counts and chunk offsets sit in the fixed part, which every packet buffer holds
-                if (in_scan) c[q] = w8 ? uint32_t(pk[ld.counts_offset + b])
-                                       : uint32_t(reinterpret_cast<const uint16_t *>(pk + ld.counts_offset)[b]);
-                coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
-                if (lane == 0) {
-                    const adacomp_packet_layer_t *rec =
-                        reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
-                    s_scale[kk] = rec->scale;
-                    s_words[kk] = uint64_t(reinterpret_cast<uintptr_t>(pk)) + rec->words_offset;
-                }
-            }
-        }
-#pragma unroll
-        for (uint32_t q = 0; q < kPerWave; ++q) {
-            const uint32_t kk = wave + 4u * q;
-            if (kk < nk) {
-                const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
-                const uint32_t incl = wave_incl_scan(cq, lane);
-                if (in_tile) {
-                    s_start[kk][b - ut.first_bin] = coff[q] + incl - cq;
-                    s_cnt[kk][b - ut.first_bin] = uint16_t(cq);
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- phase 2: a lane group owns a bin --------------------------------------------------
-        for (uint32_t s = tid; s < (nb << glog); s += kWG) {
-            const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
-            const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
-            float *acc = s_acc + lb * T;
-            uint32_t word[kLearnerGroup];
-            bool big = false;
-#pragma unroll
-            for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
-                word[kk] = 0u;
-                if (kk < nk) {
-                    const uint32_t cc = s_cnt[kk][lb];
-                    big |= cc > gsz;
-                    if (sub < cc) {
-                        const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
-                        const uint32_t at = s_start[kk][lb] + sub;
-                        word[kk] = w8 ? uint32_t(wp[at]) : uint32_t(reinterpret_cast<const uint16_t *>(wp)[at]);
-                    }
-                }
-            }
-            if (!big) {
-#pragma unroll
-                for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
-                    const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
-                    const uint32_t code = word[kk] & 3u;
-                    if ((code & 1u) && idx < span) acc[idx] += code == 1u ? s_scale[kk] : -s_scale[kk];
-                }
-            } else {
-                // some learner sends more words from this bin than the group has lanes: plain loops,
-                // one learner after the other (same order)
-                for (uint32_t kk = 0; kk < nk; ++kk) {
-                    const uint32_t cc = s_cnt[kk][lb], st = s_start[kk][lb];
-                    const float sc = s_scale[kk];
-                    const uint8_t *wp = reinterpret_cast<const uint8_t *>(uintptr_t(s_words[kk]));
-                    for (uint32_t jw = sub; jw < cc; jw += gsz) {
-                        const uint32_t wd = w8 ? uint32_t(wp[st + jw]) : uint32_t(reinterpret_cast<const uint16_t *>(wp)[st + jw]);
-                        const uint32_t idx = (wd >> 2) - ut.idx_lo;
-                        const uint32_t code = wd & 3u;
-                        if ((code & 1u) && idx < span) acc[idx] += code == 1u ? sc : -sc;
-                    }
-                }
-            }
-        }
-    }
+    if (ld.word_bytes == 1u) unpack_tile<true>(a, ut, ld, s_acc, s_off, s_cnt, s_scale, &s_cmax);
+    else unpack_tile<false>(a, ut, ld, s_acc, s_off, s_cnt, s_scale, &s_cmax);
     __syncthreads();
 
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
@@ -577,24 +653,33 @@ __global__ __launch_bounds__(kWG) void k_copy(float *__restrict__ dst, const flo
 // ---- launchers ---------------------------------------------------------------------------------
 static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK : ADACOMP_EHIP; }
 
+static uint32_t fused_extra_lds()
+{
+    static const uint32_t v = [] { const char *e = std::getenv("ADACOMP_FUSED_LDS"); return uint32_t(e ? std::atoi(e) : 0); }();
+    return v;
+}
+
 int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
-    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
-    else hipLaunchKernelGGL(k_fused<16>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    const dim3 grid(a.n_tiles * a.n_learners), wg(kWG);
+    const uint32_t lds = fused_extra_lds();
+    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, grid, wg, lds, s, a);
+    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, grid, wg, lds, s, a);
+    else if (jcode == 2) hipLaunchKernelGGL(k_fused<16>, grid, wg, lds, s, a);
+    else hipLaunchKernelGGL(k_fused<2>, grid, wg, lds, s, a);
     return check_launch();
 }
 
 int launch_scan(const CompressArgs &a, void *stream)
 {
-    hipLaunchKernelGGL(k_scan, dim3(a.n_layers), dim3(kScanWG), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(k_scan, dim3(a.n_layers, a.n_learners), dim3(kScanWG), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }
 
 int launch_place(const CompressArgs &a, void *stream)
 {
-    hipLaunchKernelGGL(k_place, dim3((a.n_tiles + kPlaceTiles - 1u) / kPlaceTiles + 1u), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(k_place, dim3((a.n_tiles + kPlaceTiles - 1u) / kPlaceTiles + 1u, a.n_learners), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }
 

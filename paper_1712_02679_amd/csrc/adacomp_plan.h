@@ -36,7 +36,7 @@ struct TileDev {
     uint32_t magic;       // floor(2^32 / L_T) + 1: bin = umulhi(e, magic) for e < 16384 (L_T > 1)
     uint32_t n_bins;      // bins in the tile, <= kMaxTileBins
     uint32_t first_bin;   // index of the tile's first bin inside the layer
-    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16), bit 31 aligned
+    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16, 3: J=2), bit 31 aligned
     __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
     __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 3u; }
     __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
@@ -59,15 +59,27 @@ struct UTileDev {
 };
 static_assert(sizeof(UTileDev) == 32, "UTileDev layout");
 
-// Byte offsets of everything inside the caller's workspace.
+// What k_fused leaves per tile for k_scan and k_place: one 16-byte record, so that a tile makes one
+// small store here instead of three.
+struct TileOut {
+    double gmax_sum;  // sum of the tile's g_max values
+    uint32_t count;   // words the tile sends
+    uint32_t base;    // words of the layer before this tile (written by k_scan)
+};
+static_assert(sizeof(TileOut) == 16, "TileOut layout");
+
+// Byte offsets inside the caller's workspace.  The tables come first; then one scratch block per
+// learner of a batched call (a single-learner call uses block 0).
 struct WorkspaceLayout {
     size_t layers = 0, ctiles = 0, utiles = 0;          // tables written by workspace_init
-    size_t tile_count = 0, tile_base = 0, tile_sum = 0; // per compress tile: words, first word in layer, sum of g_max
+    size_t scratch = 0;                                 // first scratch block
+    size_t scratch_stride = 0;                          // bytes per learner
+    // offsets inside a scratch block
+    size_t tile_out = 0;                                // TileOut per compress tile
     size_t layer_nsel = 0, layer_scale = 0;             // per layer
     size_t gmax = 0, chunk_rel = 0;                     // per bin / per chunk
     size_t stage = 0;                                   // uint16 per element: words before placement
-    size_t stage_g = 0;                                 // float per element: G of the staged words
-    size_t total = 0;
+    size_t total(size_t n_learners) const { return scratch + scratch_stride * n_learners; }
 };
 
 struct Plan {
@@ -78,7 +90,7 @@ struct Plan {
     uint64_t n_elems_total = 0;
     uint64_t fixed_bytes = 0;   // packet bytes before the first word
     uint64_t bound_bytes = 0;   // packet bytes with every element sent
-    bool has_class[3] = {false, false, false};
+    bool has_class[4] = {false, false, false, false};
     uint64_t table_hash = 0;
     WorkspaceLayout ws;
     std::vector<LayerDev> layers;
@@ -93,23 +105,21 @@ uint32_t bin_magic(uint32_t L_T);
 int default_register_class();
 
 // ---- kernel launchers (adacomp_kernels.hip) ---------------------------------------------------
+constexpr uint32_t kMaxBatch = 32;  // learners per launch of the compress kernels
+
 struct CompressArgs {
     const TileDev *tiles;
     const LayerDev *layers;
-    const float *grad;
-    float *residue;
-    uint8_t *packet;
-    uint64_t capacity;
-    uint32_t *tile_count, *tile_base;
-    double *tile_sum;
-    uint32_t *layer_nsel;
-    float *layer_scale;
-    float *gmax;
-    uint32_t *chunk_rel;
-    uint16_t *stage;
-    uint32_t *stage_g;
-    uint32_t n_tiles, n_layers;
+    uint8_t *scratch;         // scratch block of learner 0 of this launch
+    uint64_t scratch_stride;
+    uint32_t o_tile_out, o_layer_nsel, o_layer_scale, o_gmax, o_chunk_rel;
+    uint32_t n_tiles, n_layers, n_learners, keep_gmax;
+    uint64_t o_stage;
+    uint64_t capacity;        // bytes available in each packet buffer
     uint64_t fixed_bytes;
+    const float *grad[kMaxBatch];
+    float *residue[kMaxBatch];
+    uint8_t *packet[kMaxBatch];
 };
 
 struct UnpackArgs {

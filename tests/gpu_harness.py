@@ -29,10 +29,12 @@ def say(msg):
 class GpuSide:
     """Device buffers of n learners for one layer table."""
 
-    def __init__(self, table, n_total, n_learners, capacity=None):
+    def __init__(self, table, n_total, n_learners, capacity=None, batch=False):
         self.table, self.n_total = table, n_total
-        self.ws = torch.zeros(A.adacomp_workspace_bytes(table), dtype=torch.uint8, device=DEV)
+        ws_bytes = A.adacomp_workspace_bytes_batch(table, n_learners) if batch else A.adacomp_workspace_bytes(table)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV)
         A.adacomp_workspace_init(table, self.ws)
+        A.adacomp_debug_keep_gmax(True)   # the tests look at the g_max vector
         self.bound = A.adacomp_packet_bound(table)
         self.capacity = self.bound if capacity is None else capacity
         self.residue = [torch.zeros(n_total, dtype=torch.float32, device=DEV) for _ in range(n_learners)]
@@ -48,14 +50,24 @@ class GpuSide:
         torch.cuda.synchronize()
         return self.packets[k].cpu().numpy()
 
+    def compress_batch(self, grads_np):
+        """One adacomp_compress_batch call over all learners; returns their packet buffers."""
+        g = [torch.from_numpy(x).to(DEV) for x in grads_np]
+        for p in self.packets:
+            p.fill_(POISON)
+        A.adacomp_compress_batch(self.table, g, self.residue, self.packets, self.ws, packet_capacity=self.capacity)
+        torch.cuda.synchronize()
+        return [p.cpu().numpy() for p in self.packets]
+
     def unpack(self, ks):
         self.dense.fill_(float("nan"))
         A.adacomp_unpack_accumulate(self.table, [self.packets[k] for k in ks], self.dense, self.ws)
         torch.cuda.synchronize()
         return self.dense.cpu().numpy()
 
-    def gmax(self):
-        off, n = A.adacomp_workspace_gmax(self.table)
+    def gmax(self, learner=0):
+        off, n, stride = A.adacomp_workspace_gmax(self.table)
+        off += stride * learner
         return self.ws[off:off + 4 * n].cpu().numpy().view(np.float32)
 
     def close(self):
@@ -106,33 +118,41 @@ def compare_residue(got, want, mask, scale_hint, tag):
 
 
 def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, grads=None,
-               check_gmax=True, unpack_every_step=True, threads=8, label=None):
+               check_gmax=True, unpack_every_step=True, threads=8, label=None, batch=False):
     """Free-running (default) or step-locked comparison of GPU and oracle over several steps.
     grads: optional callable (learner, step) -> numpy float32 array overriding the generator."""
     label = label or wl.name
     table, n_total = wl.table(), wl.n_total
     mask = layer_mask(table, n_total)
-    gpu = GpuSide(table, n_total, n_learners)
+    gpu = GpuSide(table, n_total, n_learners, batch=batch)
     R_cpu = [np.zeros(n_total, np.float32) for _ in range(n_learners)]
     stats = []
     try:
         for t in range(n_steps):
             cpu_packets = []
+            if batch:   # all learners in one adacomp_compress_batch call, compared one by one below
+                say(f"{label} step {t} batch of {n_learners}")
+                all_g = [grads(k, t) if grads else W.gradient(wl, k, t, seed=seed, threads=threads)
+                         for k in range(n_learners)]
+                if step_locked:
+                    for k in range(n_learners):
+                        gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
+                batch_bufs = gpu.compress_batch(all_g)
             for k in range(n_learners):
                 tag = f"{label} step {t} learner {k}"
                 say(tag)
-                g = grads(k, t) if grads else W.gradient(wl, k, t, seed=seed, threads=threads)
-                if step_locked:
+                g = all_g[k] if batch else (grads(k, t) if grads else W.gradient(wl, k, t, seed=seed, threads=threads))
+                if step_locked and not batch:
                     gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
                 R_before = R_cpu[k].copy() if check_gmax else None
                 want = oracle_lib.compress(table, g, R_cpu[k])
-                got_buf = gpu.compress(k, g)
+                got_buf = batch_bufs[k] if batch else gpu.compress(k, g)
                 if check_gmax:
                     G = R_before + g
                     expect = np.concatenate([
                         np.abs(np.pad(G[off:off + n], (0, (-n) % T))).reshape(-1, T).max(axis=1)
                         for off, n, T in table])
-                    assert np.array_equal(gpu.gmax().view(np.uint32), expect.view(np.uint32)), f"{tag}: g_max"
+                    assert np.array_equal(gpu.gmax(k if batch else 0).view(np.uint32), expect.view(np.uint32)), f"{tag}: g_max"
                 compare_packet(got_buf, want, gpu.capacity, tag)
                 h, layers = pf.parse(want, check=False)
                 scale_hint = max(float(l["rec"]["scale"]) for l in layers)

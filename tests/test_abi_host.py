@@ -53,7 +53,7 @@ def test_sizes_follow_the_container_layout(L):
         assert binding.adacomp_packet_fixed_bytes(t) == fixed
         assert binding.adacomp_packet_bound(t) == fixed + words
         ws = binding.adacomp_workspace_bytes(t)
-        assert ws > 6 * W.workload(i).n_total and ws < 6.5 * W.workload(i).n_total + (1 << 20)
+        assert ws > 2 * W.workload(i).n_total and ws < 2.5 * W.workload(i).n_total + (1 << 20)
 
 
 def test_bad_tables_are_refused(L):

@@ -147,6 +147,69 @@ def test_edge_tables(H, oracle_lib, name):
     H.run_parity(oracle_lib, wl, 3, 4, seed=7, label=name)
 
 
+# ------------------------------------------------------------------------------------------------
+# batched compress: several learners per launch
+# ------------------------------------------------------------------------------------------------
+def test_batch_workload2(H, oracle_lib):
+    wl = W.workload(2)
+    H.run_parity(oracle_lib, wl, wl.n_learners, 6, batch=True)
+
+
+def test_batch_workload4_eight_learners(H, oracle_lib):
+    wl = W.workload(4)
+    H.run_parity(oracle_lib, wl, wl.n_learners, 3, batch=True, check_gmax=False)
+
+
+@pytest.mark.parametrize("name", ["mixed_with_gaps", "LT16384_and_odd_16383", "tiny_layers", "LT64_LT65_word_width"])
+def test_batch_edge_tables(H, oracle_lib, name):
+    wl = W.custom(name, EDGE_TABLES[name], dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 5, 3, seed=11, label="batch " + name, batch=True)
+
+
+def test_batch_more_learners_than_one_launch_holds(H, oracle_lib):
+    wl = W.custom("batch40", [("a", 50 * 40 + 7, 50), ("b", 500 * 12 + 11, 500)])
+    H.run_parity(oracle_lib, wl, 40, 2, seed=3, batch=True, check_gmax=False)
+
+
+def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
+    """The launch configuration bench.py times: 16 learners of the 125 M-element table in one
+    adacomp_compress_batch call.  Learners 0 and 15 are compared with the oracle element by
+    element; all 16 packets must equal what 16 single adacomp_compress calls produce."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(5)
+    table, n_total = wl.table(), wl.n_total
+    mask = G.layer_mask(table, n_total)
+    n = 16
+    gpu = G.GpuSide(table, n_total, n, batch=True)
+    try:
+        grads = [torch.from_numpy(W.gradient(wl, k, 0, threads=16)).to(G.DEV) for k in range(n)]
+        for p in gpu.packets:
+            p.fill_(G.POISON)
+        A.adacomp_compress_batch(table, grads, gpu.residue, gpu.packets, gpu.ws)
+        torch.cuda.synchronize()
+        for k in (0, 15):
+            G.say(f"speech_dnn batch learner {k} vs oracle")
+            R = np.zeros(n_total, f32)
+            want = oracle_lib.compress(table, grads[k].cpu().numpy(), R)
+            G.compare_packet(gpu.packets[k].cpu().numpy(), want, gpu.capacity, f"batch learner {k}")
+            G.compare_residue(gpu.residue[k].cpu().numpy(), R, mask, 1.0, f"batch learner {k}")
+        single = G.GpuSide(table, n_total, 1)
+        try:
+            for k in range(n):
+                G.say(f"speech_dnn batch learner {k} vs single call")
+                single.residue[0].zero_()
+                single.packets[0].fill_(G.POISON)
+                A.adacomp_compress(table, grads[k], single.residue[0], single.packets[0], single.ws)
+                torch.cuda.synchronize()
+                assert torch.equal(single.packets[0], gpu.packets[k]), k
+                assert torch.equal(single.residue[0].view(torch.int32), gpu.residue[k].view(torch.int32)), k
+        finally:
+            single.close()
+    finally:
+        gpu.close()
+
+
 def test_ties_and_zeros(H, oracle_lib):
     """Coarse dyadic grid: many equal magnitudes, exact cancellations to +-0, all-zero bins."""
     wl = W.custom("ties", [("a", 50 * 300 + 11, 50), ("b", 500 * 40 + 3, 500)])
