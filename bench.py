@@ -56,10 +56,10 @@ def main():
     ap.add_argument("--learners", type=int, default=0, help="override the workload's learner count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
-    ap.add_argument("--batch", choices=["auto", "on", "off"], default="auto",
-                    help="on: one adacomp_compress_batch call per step; off: one adacomp_compress call per learner; "
-                         "auto: batch when the gradient is below 64 M elements (launch-bound workloads), single "
-                         "calls above (the streaming kernel sustains a higher rate in launches of one learner)")
+    ap.add_argument("--batch", choices=["on", "off"], default="on",
+                    help="on: one adacomp_compress_batch call per step (the library launches the streaming kernel "
+                         "once per learner for large gradients and once per call for small ones; scan and placement "
+                         "cover all learners); off: one adacomp_compress call per learner")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (simulated learners are separate buffers on "
@@ -80,7 +80,7 @@ def main():
     n_learners = args.learners or wl.n_learners
     table, n_total, n_params = wl.table(), wl.n_total, wl.n_params
     K, Wm = args.steps, args.warmup
-    args.no_batch = args.batch == "off" or (args.batch == "auto" and n_params >= 64_000_000)
+    args.no_batch = args.batch == "off"
     threads = min(16, os.cpu_count() or 1)
 
     # ---- inputs: one seeded gradient buffer per learner; learner k uses buffer (k + t) mod n at
@@ -153,7 +153,7 @@ def main():
 
     # ---- timed region ------------------------------------------------------------------------------
     use_events = not args.no_kernel_events
-    A.adacomp_timing_enable(use_events)
+    A.adacomp_timing_enable(5 if use_events else 0)   # every 5th k_fused launch: rotates through the learners
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -165,8 +165,8 @@ def main():
         ev[t][2].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    fused_ms, fused_n = A.adacomp_timing_read() if use_events else (0.0, 0)
-    A.adacomp_timing_enable(False)
+    fused_ms, fused_n, fused_learners = A.adacomp_timing_read() if use_events else (0.0, 0, 0)
+    A.adacomp_timing_enable(0)
 
     compress_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in range(K)) / K
     unpack_ms = sum(ev[t][1].elapsed_time(ev[t][2]) for t in range(K)) / K
@@ -190,7 +190,7 @@ def main():
     ratio_wire = 4.0 * n_params * n_learners / max(1, total_bytes)
 
     # ---- roofline of the dominant kernel ------------------------------------------------------------
-    per_launch = 1 if args.no_batch else n_learners  # learners one k_fused launch covers
+    per_launch = fused_learners // fused_n if fused_n else 1  # learners one k_fused launch covers
     alg_bytes_launch = 12 * n_params * per_launch  # k_fused: read dW, read residue, write residue, 4 B each
     roofline = None
     if use_events and fused_n:

@@ -185,11 +185,13 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
  * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
 int adacomp_selftest_binindex(void);
 
-/* Per-kernel timing of the streaming kernel of adacomp_compress / adacomp_compress_batch (one
- * launch per call, covering all learners of the call) with HIP events on the caller's stream.  enable != 0 starts recording (and clears earlier records); adacomp_timing_read
- * synchronises the recorded events and returns their summed duration and count. */
+/* Per-kernel timing of the streaming kernel (k_fused) of adacomp_compress / adacomp_compress_batch
+ * with HIP events on the caller's stream.  enable = k > 0 starts recording every k-th launch (and
+ * clears earlier records; an event pair costs a few microseconds between back-to-back launches, so
+ * a timed run samples); 0 stops.  adacomp_timing_read synchronises the recorded events and returns their
+ * summed duration, the number of launches and the number of learners those launches covered. */
 int adacomp_timing_enable(int enable);
-int adacomp_timing_read(double *total_ms, uint64_t *n_launches);
+int adacomp_timing_read(double *total_ms, uint64_t *n_launches, uint64_t *n_learners);
 
 #ifdef __cplusplus
 }

@@ -72,7 +72,8 @@ def lib():
         L.adacomp_debug_keep_gmax.argtypes = [ctypes.c_int]
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
         L.adacomp_timing_enable.argtypes = [ctypes.c_int]
-        L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+        L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64),
+                                          ctypes.POINTER(ctypes.c_uint64)]
         _lib = L
     return _lib
 
@@ -171,14 +172,15 @@ def adacomp_selftest_binindex() -> int:
     return int(lib().adacomp_selftest_binindex())
 
 
-def adacomp_timing_enable(on: bool):
-    _check(lib().adacomp_timing_enable(1 if on else 0))
+def adacomp_timing_enable(every: int):
+    """0: off; k > 0: record every k-th launch of the streaming kernel."""
+    _check(lib().adacomp_timing_enable(int(every)))
 
 
 def adacomp_timing_read():
-    ms, n = ctypes.c_double(), ctypes.c_uint64()
-    _check(lib().adacomp_timing_read(ctypes.byref(ms), ctypes.byref(n)))
-    return ms.value, n.value
+    ms, n, k = ctypes.c_double(), ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().adacomp_timing_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(k)))
+    return ms.value, n.value, k.value
 
 
 def read_packet_summary(packet):

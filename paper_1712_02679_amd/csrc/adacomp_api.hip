@@ -30,7 +30,7 @@ int default_register_class()
     static int cls = [] {
         const char *e = std::getenv("ADACOMP_TILE_CLASS");
         int v = e ? std::atoi(e) : 0;
-        return v < -1 ? -1 : (v > 2 ? 2 : v);   // -1: tiles of 2048 elements
+        return v < 0 ? 0 : (v > 2 ? 2 : v);
     }();
     return cls;
 }
@@ -41,7 +41,7 @@ uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers)
     auto mix = [&h](uint64_t v) { for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xFF; h *= 1099511628211ull; } };
     mix(n_layers);
     for (uint32_t l = 0; l < n_layers; ++l) { mix(layers[l].elem_offset); mix(layers[l].n_elems); mix(layers[l].L_T); }
-    mix(uint64_t(int64_t(default_register_class())));
+    mix(uint64_t(default_register_class()));
     return h;
 }
 
@@ -111,9 +111,8 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         // Tiles of 8192 elements (class 1) stream at less than half the rate of 4096 or 16384 on
         // MI355X (measured on a plain triad), so bins above 4096 go straight to class 2.
         int cls = base_cls;
-        if (cls < 0 && T > 2048u) cls = 0;
-        if (cls >= 0 && T > (4096u << cls)) cls = 2;
-        const uint32_t cap = cls < 0 ? 2048u : 4096u << cls;
+        if (T > (4096u << cls)) cls = 2;
+        const uint32_t cap = 4096u << cls;
         uint32_t bpt = cap / T;                       // >= 1
         if (bpt > kMaxTileBins) bpt = kMaxTileBins;
         const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
@@ -121,7 +120,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         const uint32_t nt = (n_bins + bpt - 1) / bpt;
         ld.ctile_start = uint32_t(n_ctiles);
         ld.n_ctiles = nt;
-        p.has_class[cls < 0 ? 3 : cls] = true;
+        p.has_class[cls] = true;
         if (tables) {
             for (uint32_t t = 0; t < nt; ++t) {
                 TileDev td;
@@ -133,7 +132,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
                 td.magic = bin_magic(T);
                 td.n_bins = (td.n_elems + T - 1) / T;
                 td.first_bin = first_bin;
-                td.layer_flags = l | (uint32_t(cls < 0 ? 3 : cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
+                td.layer_flags = l | (uint32_t(cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
                 p.ctiles.push_back(td);
             }
         }
@@ -230,7 +229,7 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
-    for (int c = 0; c < 4; ++c) out.has_class[c] = p.has_class[c];
+    for (int c = 0; c < 3; ++c) out.has_class[c] = p.has_class[c];
     out.table_hash = p.table_hash; out.ws = p.ws;
     return ADACOMP_OK;
 }
@@ -240,6 +239,9 @@ struct Timing {
     bool on = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
     size_t used = 0;
+    uint64_t learners = 0;  // learners covered by the recorded launches
+    uint32_t stride = 1;    // every stride-th launch is recorded
+    uint64_t seen = 0;      // launches since recording started
 };
 static Timing g_timing;
 static bool g_keep_gmax = false;
@@ -353,13 +355,13 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.fixed_bytes = p.fixed_bytes;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    static const uint32_t chunk = [] {
-        const char *e = std::getenv("ADACOMP_BATCH_CHUNK");
-        const int v = e ? std::atoi(e) : int(kMaxBatch);
-        return uint32_t(v < 1 ? 1 : (v > int(kMaxBatch) ? int(kMaxBatch) : v));
-    }();
-    for (uint32_t done = 0; done < n_learners; done += chunk) {
-        const uint32_t now = std::min(n_learners - done, chunk);
+    // The streaming kernel sustains its best rate in launches of a few hundred microseconds (one
+    // 16-learner launch of the 125 M-element workload ran 15 % slower per byte than 16 launches), so
+    // large gradients get one k_fused launch per learner and small ones share a launch; the scan
+    // and placement kernels always cover all learners of the call.
+    const uint32_t per_launch_max = p.n_elems_total >= kSplitElems ? 1u : kMaxBatch;
+    for (uint32_t done = 0; done < n_learners; done += kMaxBatch) {
+        const uint32_t now = std::min(n_learners - done, kMaxBatch);
         a.n_learners = now;
         a.scratch = reinterpret_cast<uint8_t *>(ws + p.ws.scratch + p.ws.scratch_stride * done);
         for (uint32_t k = 0; k < kMaxBatch; ++k) {
@@ -367,19 +369,24 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
             a.residue[k] = k < now ? residues[done + k] : nullptr;
             a.packet[k] = k < now ? static_cast<uint8_t *>(packets_out[done + k]) : nullptr;
         }
-        std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
-        if (g_timing.on) {
-            if (g_timing.used == g_timing.pool.size()) {
-                hipEvent_t e0, e1;
-                if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
-                g_timing.pool.emplace_back(e0, e1);
+        for (uint32_t f = 0; f < now; f += per_launch_max) {
+            a.fused_first = f;
+            a.fused_count = std::min(per_launch_max, now - f);
+            std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
+            if (g_timing.on && (g_timing.seen++ % g_timing.stride) == 0) {
+                if (g_timing.used == g_timing.pool.size()) {
+                    hipEvent_t e0, e1;
+                    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
+                    g_timing.pool.emplace_back(e0, e1);
+                }
+                ev = &g_timing.pool[g_timing.used++];
+                g_timing.learners += a.fused_count;
+                if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
             }
-            ev = &g_timing.pool[g_timing.used++];
-            if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
+            for (int c = 0; c < 3; ++c)
+                if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
+            if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
         }
-        for (int c = 0; c < 4; ++c)
-            if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
-        if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
         if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
         if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
@@ -471,13 +478,16 @@ int adacomp_debug_keep_gmax(int enable)
 int adacomp_timing_enable(int enable)
 {
     g_timing.on = enable != 0;
+    g_timing.stride = enable > 0 ? uint32_t(enable) : 1u;
     g_timing.used = 0;
+    g_timing.learners = 0;
+    g_timing.seen = 0;
     return ADACOMP_OK;
 }
 
-int adacomp_timing_read(double *total_ms, uint64_t *n_launches)
+int adacomp_timing_read(double *total_ms, uint64_t *n_launches, uint64_t *n_learners)
 {
-    if (!total_ms || !n_launches) return ADACOMP_EINVAL;
+    if (!total_ms || !n_launches || !n_learners) return ADACOMP_EINVAL;
     double sum = 0.0;
     for (size_t i = 0; i < g_timing.used; ++i) {
         float ms = 0.f;
@@ -488,7 +498,9 @@ int adacomp_timing_read(double *total_ms, uint64_t *n_launches)
     }
     *total_ms = sum;
     *n_launches = g_timing.used;
+    *n_learners = g_timing.learners;
     g_timing.used = 0;
+    g_timing.learners = 0;
     return ADACOMP_OK;
 }
 

@@ -21,7 +21,6 @@
 // tile is written out once with coalesced float4 stores.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "adacomp_plan.h"
@@ -89,10 +88,11 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 {
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
     // call streams one learner's buffers after the other instead of all of them at once
-    const uint32_t lr = blockIdx.x / a.n_tiles;
-    const uint32_t tile = blockIdx.x - lr * a.n_tiles;
+    const uint32_t lq = blockIdx.x / a.n_tiles;
+    const uint32_t tile = blockIdx.x - lq * a.n_tiles;
+    const uint32_t lr = a.fused_first + lq;
     const TileDev td = a.tiles[tile];
-    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : (J == 16 ? 2u : 3u)))) return;
+    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
     uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
@@ -313,10 +313,24 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
     __shared__ uint32_t s_wsum[16];
     __shared__ double s_dsum[16];
 
+    // a thread's run of tiles is read once into registers when it is short (up to 8 records: layers of
+    // up to 8192 tiles), so the kernel costs one memory round trip before the scan and one store after
+    constexpr uint32_t kHold = 8;
+    uint32_t cnt[kHold];
     uint32_t csum = 0u;
     double dsum = 0.0;
-#pragma unroll 8
-    for (uint32_t i = lo; i < hi; ++i) { const TileOut o = tile_out[ts + i]; csum += o.count; dsum += o.gmax_sum; }
+    if (per <= kHold) {
+        TileOut rec[kHold];
+#pragma unroll
+        for (uint32_t i = 0; i < kHold; ++i) {
+            rec[i].gmax_sum = 0.0; rec[i].count = 0u;
+            if (lo + i < hi) rec[i] = tile_out[ts + lo + i];
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < kHold; ++i) { cnt[i] = rec[i].count; csum += rec[i].count; dsum += rec[i].gmax_sum; }
+    } else {
+        for (uint32_t i = lo; i < hi; ++i) { const TileOut o = tile_out[ts + i]; csum += o.count; dsum += o.gmax_sum; }
+    }
 
     const uint32_t incl = wave_incl_scan(csum, lane);
     dsum = wave_sum_f64(dsum);
@@ -326,8 +340,13 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
     uint32_t wave_base = 0u;
     for (uint32_t wv = 0; wv < wave; ++wv) wave_base += s_wsum[wv];
     uint32_t run = wave_base + incl - csum;
-#pragma unroll 8
-    for (uint32_t i = lo; i < hi; ++i) { tile_out[ts + i].base = run; run += tile_out[ts + i].count; }
+    if (per <= kHold) {
+#pragma unroll
+        for (uint32_t i = 0; i < kHold; ++i)
+            if (lo + i < hi) { tile_out[ts + lo + i].base = run; run += cnt[i]; }
+    } else {
+        for (uint32_t i = lo; i < hi; ++i) { tile_out[ts + i].base = run; run += tile_out[ts + i].count; }
+    }
     if (tid == 0) {
         double total = 0.0;
         uint32_t nsel = 0u;
@@ -364,37 +383,59 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
 
     if (blockIdx.x == gridDim.x - 1) {
-        // ---- header, layer records, zero padding ------------------------------------------------
-        __shared__ uint64_t s_total, s_nsel;
-        if (tid == 0) { s_total = 0; s_nsel = 0; }
-        __syncthreads();
-        for (uint32_t l = tid; l < a.n_layers; l += kWG) {
-            const LayerDev ld = a.layers[l];
-            uint64_t woff = a.fixed_bytes;
-            for (uint32_t m = 0; m < l; ++m) woff += pad16_dev(uint64_t(layer_nsel[m]) * a.layers[m].word_bytes);
-            const uint64_t nsel = layer_nsel[l];
-            adacomp_packet_layer_t rec;
-            rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
-            rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
-            rec.scale = layer_scale[l];
-            rec.n_selected = nsel;
-            rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
-            reinterpret_cast<adacomp_packet_layer_t *>(packet + sizeof(adacomp_packet_header_t))[l] = rec;
-            for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) packet[b] = 0;
-            const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
-            for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) packet[b] = 0;
-            const uint64_t words_end = woff + nsel * ld.word_bytes;
-            for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
-                if (b < a.capacity) packet[b] = 0;
-            if (l == a.n_layers - 1) s_total = pad16_dev(words_end);
-            atomicAdd(reinterpret_cast<unsigned long long *>(&s_nsel), (unsigned long long)nsel);
+        // ---- header, layer records, zero padding: 256 layers at a time, word offsets by a block
+        //      scan of the padded section sizes (all below 2^32: the packet bound is) --------------
+        __shared__ uint32_t s_wtot[4];
+        const uint32_t lane = tid & 63u;
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        uint64_t carry = a.fixed_bytes, nsel_all = 0;
+        for (uint32_t l0 = 0; l0 < a.n_layers; l0 += kWG) {
+            const uint32_t l = l0 + tid;
+            const bool live = l < a.n_layers;
+            LayerDev ld;
+            uint32_t nsel = 0u, bytes = 0u;
+            float scale = 0.f;
+            if (live) {
+                ld = a.layers[l];
+                nsel = layer_nsel[l];
+                scale = layer_scale[l];
+                bytes = uint32_t(pad16_dev(uint64_t(nsel) * ld.word_bytes));
+            }
+            const uint32_t incl = wave_incl_scan(bytes, lane);
+            uint32_t nsum = wave_sum(nsel);
+            __syncthreads();  // previous round's readers of s_wtot are done
+            if (lane == 63) s_wtot[wave] = incl;
+            __syncthreads();
+            uint64_t before = carry;
+            for (uint32_t wv = 0; wv < wave; ++wv) before += s_wtot[wv];
+            const uint64_t woff = before + incl - bytes;
+            carry += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
+            if (live) {
+                adacomp_packet_layer_t rec;
+                rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
+                rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
+                rec.scale = scale;
+                rec.n_selected = nsel;
+                rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
+                reinterpret_cast<adacomp_packet_layer_t *>(packet + sizeof(adacomp_packet_header_t))[l] = rec;
+                for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) packet[b] = 0;
+                const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
+                for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) packet[b] = 0;
+                const uint64_t words_end = woff + uint64_t(nsel) * ld.word_bytes;
+                for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
+                    if (b < a.capacity) packet[b] = 0;
+            }
+            // total word count: per-wave sums through the same LDS slots
+            __syncthreads();
+            if (lane == 0) s_wtot[wave] = nsum;
+            __syncthreads();
+            nsel_all += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
         }
-        __syncthreads();
         if (tid == 0) {
             adacomp_packet_header_t h;
             h.magic = ADACOMP_PACKET_MAGIC; h.version = ADACOMP_PACKET_VERSION;
-            h.status = s_total > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
-            h.n_layers = a.n_layers; h.total_bytes = s_total; h.n_selected = s_nsel;
+            h.status = carry > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
+            h.n_layers = a.n_layers; h.total_bytes = carry; h.n_selected = nsel_all;
             *reinterpret_cast<adacomp_packet_header_t *>(packet) = h;
         }
         return;
@@ -653,21 +694,13 @@ __global__ __launch_bounds__(kWG) void k_copy(float *__restrict__ dst, const flo
 // ---- launchers ---------------------------------------------------------------------------------
 static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK : ADACOMP_EHIP; }
 
-static uint32_t fused_extra_lds()
-{
-    static const uint32_t v = [] { const char *e = std::getenv("ADACOMP_FUSED_LDS"); return uint32_t(e ? std::atoi(e) : 0); }();
-    return v;
-}
-
 int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(a.n_tiles * a.n_learners), wg(kWG);
-    const uint32_t lds = fused_extra_lds();
-    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, grid, wg, lds, s, a);
-    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, grid, wg, lds, s, a);
-    else if (jcode == 2) hipLaunchKernelGGL(k_fused<16>, grid, wg, lds, s, a);
-    else hipLaunchKernelGGL(k_fused<2>, grid, wg, lds, s, a);
+    const dim3 grid(a.n_tiles * a.fused_count), wg(kWG);
+    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, grid, wg, 0, s, a);
+    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, grid, wg, 0, s, a);
+    else hipLaunchKernelGGL(k_fused<16>, grid, wg, 0, s, a);
     return check_launch();
 }
 

@@ -36,7 +36,7 @@ struct TileDev {
     uint32_t magic;       // floor(2^32 / L_T) + 1: bin = umulhi(e, magic) for e < 16384 (L_T > 1)
     uint32_t n_bins;      // bins in the tile, <= kMaxTileBins
     uint32_t first_bin;   // index of the tile's first bin inside the layer
-    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16, 3: J=2), bit 31 aligned
+    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16), bit 31 aligned
     __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
     __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 3u; }
     __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
@@ -90,7 +90,7 @@ struct Plan {
     uint64_t n_elems_total = 0;
     uint64_t fixed_bytes = 0;   // packet bytes before the first word
     uint64_t bound_bytes = 0;   // packet bytes with every element sent
-    bool has_class[4] = {false, false, false, false};
+    bool has_class[3] = {false, false, false};
     uint64_t table_hash = 0;
     WorkspaceLayout ws;
     std::vector<LayerDev> layers;
@@ -106,6 +106,7 @@ int default_register_class();
 
 // ---- kernel launchers (adacomp_kernels.hip) ---------------------------------------------------
 constexpr uint32_t kMaxBatch = 32;  // learners per launch of the compress kernels
+constexpr uint64_t kSplitElems = 32u * 1000u * 1000u;  // gradients at least this long: one k_fused launch per learner
 
 struct CompressArgs {
     const TileDev *tiles;
@@ -114,6 +115,7 @@ struct CompressArgs {
     uint64_t scratch_stride;
     uint32_t o_tile_out, o_layer_nsel, o_layer_scale, o_gmax, o_chunk_rel;
     uint32_t n_tiles, n_layers, n_learners, keep_gmax;
+    uint32_t fused_first, fused_count;  // learners covered by one k_fused launch
     uint64_t o_stage;
     uint64_t capacity;        // bytes available in each packet buffer
     uint64_t fixed_bytes;

@@ -137,6 +137,7 @@ EDGE_TABLES = {
     "LT5000_LT8192": [("a", 5000 * 5 + 3, 5000), ("b", 8192 * 3, 8192)],
     "LT16384_and_odd_16383": [("a", 16384 * 3 + 5, 16384), ("b", 16383 * 2 + 7, 16383)],
     "tiny_layers": [("a", 1, 500), ("b", 2, 50), ("c", 3, 1), ("d", 5, 16384), ("e", 63, 64)],
+    "many_layers_300": [(f"l{i}", 1 + (i * 37) % 211, (1, 3, 50, 64, 65, 500)[i % 6]) for i in range(300)],
     "mixed_with_gaps": [("a", 4801, 50), ("b", 102402, 50), ("c", 786433, 500), ("d", 1923, 500), ("e", 777, 9)],
 }
 
