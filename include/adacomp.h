@@ -150,6 +150,27 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
                            const float *const *grads, float *const *residues, void *const *packets_out,
                            size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* pack() with another selection rule or soft-threshold factor: the mechanisms of the paper's
+ * ablations (section "Robustness of the AdaComp Technique": Local Selection = "similar to AdaComp's
+ * local selection scheme, but without applying a soft-threshold"; section "Adaptive Residual
+ * Gradient Compression (AdaComp) Technique": factors 1.5 - 3.0 were studied, 2 chosen so that only
+ * additions are needed).  Everything else (bins, g_max, scale, quantiser, residue, packet) is as
+ * in adacomp_compress_batch, which is this call with ADACOMP_RULE_ADACOMP and factor 2.
+ *   rule         ADACOMP_RULE_ADACOMP          sent iff G != 0 and max(|H|, |G|) >= g_max
+ *                ADACOMP_RULE_PRINTED_COMPARE  sent iff |H| >= g_max, exactly the compare printed in
+ *                                              Algorithm 2 (may drop a bin maximum, sends zeros of
+ *                                              an all-zero bin)
+ *                ADACOMP_RULE_LOCAL_SELECTION  sent iff G != 0 and |G| >= g_max (bin maxima only)
+ *   soft_factor  f in [1, 16]: H = residue + f dW, computed as G + (f - 1) dW with one float
+ *                multiplication and one addition; f = 2 is G + dW.  Other values: ADACOMP_EINVAL. */
+#define ADACOMP_RULE_ADACOMP 0u
+#define ADACOMP_RULE_PRINTED_COMPARE 1u
+#define ADACOMP_RULE_LOCAL_SELECTION 2u
+int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                             const float *const *grads, float *const *residues, void *const *packets_out,
+                             size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
 /* ---- unpack() of all learners, summed ("unpack()" then the sum inside "averageGradients()") -- */
 
 /* packets    HOST array of n_learners DEVICE pointers to complete packets made by

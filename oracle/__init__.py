@@ -51,12 +51,12 @@ class Oracle:
         fp = ctypes.POINTER(ctypes.c_float)
         L.adacomp_oracle_pack_layer.restype = ctypes.c_longlong
         L.adacomp_oracle_pack_layer.argtypes = [fp, fp, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
-                                                fp, fp, fp, fp, ctypes.POINTER(ctypes.c_uint8), fp]
+                                                ctypes.c_float, fp, fp, fp, fp, ctypes.POINTER(ctypes.c_uint8), fp]
         L.adacomp_oracle_packet_bound.restype = ctypes.c_size_t
         L.adacomp_oracle_packet_bound.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32]
         L.adacomp_oracle_compress.restype = ctypes.c_longlong
         L.adacomp_oracle_compress.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32, fp, fp,
-                                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+                                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float]
         L.adacomp_oracle_unpack_accumulate.restype = ctypes.c_int
         L.adacomp_oracle_unpack_accumulate.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32,
                                                        ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32, fp]
@@ -66,7 +66,7 @@ class Oracle:
         assert a.dtype == np.float32 and a.flags.c_contiguous
         return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
 
-    def pack_layer(self, residue, dW, T, rule=RULE_UNION):
+    def pack_layer(self, residue, dW, T, rule=RULE_UNION, soft_factor=2.0):
         """One layer of Algorithm 2.  Returns a dict of every intermediate value."""
         residue = np.ascontiguousarray(residue, dtype=np.float32)
         dW = np.ascontiguousarray(dW, dtype=np.float32)
@@ -78,7 +78,7 @@ class Oracle:
         scale = np.zeros(1, np.float32)
         sel = np.empty(n, np.uint8)
         R_new = np.empty(n, np.float32)
-        rc = self.lib.adacomp_oracle_pack_layer(self._f(residue), self._f(dW), n, T, rule, self._f(G),
+        rc = self.lib.adacomp_oracle_pack_layer(self._f(residue), self._f(dW), n, T, rule, soft_factor, self._f(G),
                                                 self._f(H), self._f(gmax), self._f(scale),
                                                 sel.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
                                                 self._f(R_new))
@@ -90,7 +90,7 @@ class Oracle:
     def packet_bound(self, layers) -> int:
         return int(self.lib.adacomp_oracle_packet_bound(_layer_array(layers), len(layers)))
 
-    def compress(self, layers, grad, residue, capacity=None, rule=RULE_UNION):
+    def compress(self, layers, grad, residue, capacity=None, rule=RULE_UNION, soft_factor=2.0):
         """pack() over a layer table; ``residue`` (numpy float32) is updated in place.
         Returns the packet as a uint8 array of exactly total_bytes.  Raises on error codes."""
         assert grad.dtype == np.float32 and residue.dtype == np.float32
@@ -98,10 +98,10 @@ class Oracle:
         cap = self.packet_bound(layers) if capacity is None else int(capacity)
         if cap == 0:
             raise OracleError(self.lib.adacomp_oracle_compress(
-                _layer_array(layers), len(layers), self._f(grad), self._f(residue), None, 0, rule))
+                _layer_array(layers), len(layers), self._f(grad), self._f(residue), None, 0, rule, soft_factor))
         buf = np.zeros(cap, np.uint8)
         rc = self.lib.adacomp_oracle_compress(_layer_array(layers), len(layers), self._f(grad),
-                                              self._f(residue), buf.ctypes.data, cap, rule)
+                                              self._f(residue), buf.ctypes.data, cap, rule, soft_factor)
         if rc < 0:
             raise OracleError(rc)
         return buf[:rc].copy()

@@ -22,20 +22,31 @@
  * Algorithm 2, one layer.
  * ---------------------------------------------------------------------------------------- */
 long long adacomp_oracle_pack_layer(const float *residue_in, const float *dW, uint64_t n, uint32_t T,
-                                    int rule, float *G, float *H, float *gmax, float *scale,
-                                    uint8_t *selected, float *residue_out)
+                                    int rule, float soft_factor, float *G, float *H, float *gmax,
+                                    float *scale, uint8_t *selected, float *residue_out)
 {
     if (!residue_in || !dW || !G || !H || !gmax || !scale || !selected || !residue_out) return -1;
     if (n == 0 || T == 0 || T > LT_MAX) return -1;
     if (rule < 0 || rule > 2) return -1;
+    if (!(soft_factor >= 1.0f && soft_factor <= 16.0f)) return -1;
 
     uint64_t n_bins = (n + T - 1) / T; /* last bin may be short */
 
     /* G <- residue + dW */
     for (uint64_t index = 0; index < n; ++index) G[index] = residue_in[index] + dW[index];
 
-    /* H <- G + dW   (two float additions: the stored G is used) */
-    for (uint64_t index = 0; index < n; ++index) H[index] = G[index] + dW[index];
+    /* H <- G + dW   (two float additions: the stored G is used).  That is residue + 2 dW, the
+     * paper's choice among the factors 1.5 - 3.0 it studied; for another factor f the operand is
+     * residue + f dW, formed as G + (f - 1) dW with one multiplication and one addition. */
+    if (soft_factor == 2.0f) {
+        for (uint64_t index = 0; index < n; ++index) H[index] = G[index] + dW[index];
+    } else {
+        float f_minus_1 = soft_factor - 1.0f;
+        for (uint64_t index = 0; index < n; ++index) {
+            float extra = f_minus_1 * dW[index];
+            H[index] = G[index] + extra;
+        }
+    }
 
     /* first loop over bins: g_max(i) = largest absolute value of G in bin i */
     for (uint64_t i = 0; i < n_bins; ++i) {
@@ -146,7 +157,7 @@ size_t adacomp_oracle_packet_bound(const adacomp_oracle_layer_t *layers, uint32_
 
 long long adacomp_oracle_compress(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
                                   const float *grad, float *residue, void *packet_out,
-                                  size_t packet_capacity, int rule)
+                                  size_t packet_capacity, int rule, float soft_factor)
 {
     int rc = check_layers(layers, n_layers);
     if (rc != 0) return rc;
@@ -172,7 +183,7 @@ long long adacomp_oracle_compress(const adacomp_oracle_layer_t *layers, uint32_t
         if (!H || !gmax || !tmp[l].G || !tmp[l].R_new || !tmp[l].sel) ok = 0;
         if (ok) {
             tmp[l].n_sent = adacomp_oracle_pack_layer(residue + layers[l].elem_offset,
-                                                      grad + layers[l].elem_offset, n, T, rule,
+                                                      grad + layers[l].elem_offset, n, T, rule, soft_factor,
                                                       tmp[l].G, H, gmax, &tmp[l].scale, tmp[l].sel,
                                                       tmp[l].R_new);
             if (tmp[l].n_sent < 0) ok = 0;

@@ -77,11 +77,14 @@ typedef struct {
 
 /* One layer, one mini-batch of Algorithm 2.  All arrays are host memory.  residue_in and
  * residue_out may be the same array.  G, H (n floats), gmax (ceil(n/T) floats), selected (n bytes,
- * 0 or 1) and scale receive the intermediate values; none of them may be NULL.
+ * 0 or 1) and scale receive the intermediate values; none of them may be NULL.  soft_factor is
+ * the multiple of dW in the soft-threshold operand (section "Adaptive Residual Gradient
+ * Compression (AdaComp) Technique": factors 1.5 - 3.0 were studied, 2 chosen), 1 <= f <= 16;
+ * 2.0f gives H = G + dW exactly as printed.
  * Returns the number of selected elements, or -1 on a bad argument. */
 long long adacomp_oracle_pack_layer(const float *residue_in, const float *dW, uint64_t n, uint32_t T,
-                                    int rule, float *G, float *H, float *gmax, float *scale,
-                                    uint8_t *selected, float *residue_out);
+                                    int rule, float soft_factor, float *G, float *H, float *gmax,
+                                    float *scale, uint8_t *selected, float *residue_out);
 
 /* Size of the packet when every element of every layer is selected; 0 on a bad layer table. */
 size_t adacomp_oracle_packet_bound(const adacomp_oracle_layer_t *layers, uint32_t n_layers);
@@ -92,7 +95,7 @@ size_t adacomp_oracle_packet_bound(const adacomp_oracle_layer_t *layers, uint32_
  * untouched). */
 long long adacomp_oracle_compress(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
                                   const float *grad, float *residue, void *packet_out,
-                                  size_t packet_capacity, int rule);
+                                  size_t packet_capacity, int rule, float soft_factor);
 
 /* unpack() of n_learners packets summed into dense_out in learner order 0..n-1 (float adds);
  * every element of every layer is written (0 where no learner sent it).  Returns 0, or -1 on a

@@ -19,7 +19,7 @@ OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 EXPORTS = [
     "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
     "adacomp_workspace_bytes_batch", "adacomp_workspace_init", "adacomp_workspace_release",
-    "adacomp_compress", "adacomp_compress_batch",
+    "adacomp_compress", "adacomp_compress_batch", "adacomp_compress_variant",
     "adacomp_unpack_accumulate", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
     "adacomp_selftest_binindex", "adacomp_timing_enable", "adacomp_timing_read",
@@ -62,6 +62,8 @@ def lib():
         L.adacomp_workspace_bytes_batch.argtypes = [LP, u32, u32]
         L.adacomp_compress_batch.argtypes = [LP, u32, u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                              ctypes.POINTER(vp), sz, vp, sz, vp]
+        L.adacomp_compress_variant.argtypes = [LP, u32, u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                               ctypes.POINTER(vp), sz, u32, ctypes.c_float, vp, sz, vp]
         L.adacomp_workspace_init.argtypes = [LP, u32, vp, sz, vp]
         L.adacomp_workspace_release.argtypes = [vp]
         L.adacomp_compress.argtypes = [LP, u32, vp, vp, vp, sz, vp, sz, vp]
@@ -143,6 +145,23 @@ def adacomp_compress_batch(layers, grads, residues, packets_out, workspace, pack
     p = (vp * n)(*[t.data_ptr() for t in packets_out])
     _check(lib().adacomp_compress_batch(layer_array(layers), len(layers), n, g, r, p, cap, _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
+
+
+RULE_ADACOMP, RULE_PRINTED_COMPARE, RULE_LOCAL_SELECTION = 0, 1, 2
+
+
+def adacomp_compress_variant(layers, grads, residues, packets_out, workspace, rule=RULE_ADACOMP, soft_factor=2.0,
+                             packet_capacity=None):
+    """adacomp_compress_batch with another selection rule or soft-threshold factor."""
+    n = len(grads)
+    cap = min(p.numel() for p in packets_out) if packet_capacity is None else int(packet_capacity)
+    vp = ctypes.c_void_p
+    g = (vp * n)(*[t.data_ptr() for t in grads])
+    r = (vp * n)(*[t.data_ptr() for t in residues])
+    p = (vp * n)(*[t.data_ptr() for t in packets_out])
+    _check(lib().adacomp_compress_variant(layer_array(layers), len(layers), n, g, r, p, cap, int(rule),
+                                          ctypes.c_float(soft_factor), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()))
 
 
 def adacomp_unpack_accumulate(layers, packets, dense_out, workspace):

@@ -322,11 +322,13 @@ int adacomp_workspace_release(void *workspace)
     return g_ws.erase(workspace) ? ADACOMP_OK : ADACOMP_EINVAL;
 }
 
-int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
-                           const float *const *grads, float *const *residues, void *const *packets_out,
-                           size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream)
+int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                             const float *const *grads, float *const *residues, void *const *packets_out,
+                             size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
+                             size_t workspace_bytes, void *hip_stream)
 {
     if (n_learners == 0 || !grads || !residues || !packets_out) return ADACOMP_EINVAL;
+    if (rule > ADACOMP_RULE_LOCAL_SELECTION || !(soft_factor >= 1.0f && soft_factor <= 16.0f)) return ADACOMP_EINVAL;
     for (uint32_t k = 0; k < n_learners; ++k) {
         if (!grads[k] || !residues[k] || !packets_out[k] || grads[k] == residues[k]) return ADACOMP_EINVAL;
         if (reinterpret_cast<uintptr_t>(grads[k]) % 16 || reinterpret_cast<uintptr_t>(residues[k]) % 16 ||
@@ -351,6 +353,8 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
     a.keep_gmax = g_keep_gmax ? 1u : 0u;
+    a.rule = rule;
+    a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;
     a.fixed_bytes = p.fixed_bytes;
 
@@ -391,6 +395,14 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
         if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
     return ADACOMP_OK;
+}
+
+int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                           const float *const *grads, float *const *residues, void *const *packets_out,
+                           size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return adacomp_compress_variant(layers, n_layers, n_learners, grads, residues, packets_out, packet_capacity,
+                                    ADACOMP_RULE_ADACOMP, 2.0f, workspace, workspace_bytes, hip_stream);
 }
 
 int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,

@@ -83,7 +83,9 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // k_fused: Algorithm 2, both loops, on a tile of whole bins held in registers.
 // Thread t owns float4 slots t, t + 256, ...: element e = 4 * (j * 256 + t) + c of the tile.
 // ==============================================================================================
-template <int J>
+// VARIANT = false is the method as built by default (union rule, factor 2: additions only);
+// VARIANT = true takes the selection rule and the soft-threshold factor from the arguments.
+template <int J, bool VARIANT>
 __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 {
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
@@ -147,10 +149,18 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             G[c] = r[j][c] + w[j][c];
-            const float H = G[c] + w[j][c];
+            float H;
+            if (VARIANT) {
+                const float extra = a.soft_factor_minus_1 * w[j][c];  // residue + f dW = G + (f - 1) dW
+                H = G[c] + extra;
+            } else {
+                H = G[c] + w[j][c];
+            }
             gb[j][c] = __float_as_uint(G[c]);
             const uint32_t ag = gb[j][c] & 0x7FFFFFFFu, ah = __float_as_uint(H) & 0x7FFFFFFFu;
-            mb[j][c] = ag > ah ? ag : ah;
+            if (VARIANT && a.rule == ADACOMP_RULE_PRINTED_COMPARE) mb[j][c] = ah;          // |H| alone
+            else if (VARIANT && a.rule == ADACOMP_RULE_LOCAL_SELECTION) mb[j][c] = ag;     // bin maxima only
+            else mb[j][c] = ag > ah ? ag : ah;
         }
         if (vec && e0 + 4u <= n) {
             store_stream4(rs + e0, vfloat4{G[0], G[1], G[2], G[3]});
@@ -198,7 +208,10 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
                 const uint32_t e = e0 + uint32_t(c);
                 if (e < n) {
                     const uint32_t gm = s_gmax[bin_of(e, T, M)];
-                    const bool sent = ((gb[j][c] & 0x7FFFFFFFu) != 0u) && (mb[j][c] >= gm);
+                    // the printed compare alone also sends elements whose G is zero
+                    const bool nonzero = (gb[j][c] & 0x7FFFFFFFu) != 0u ||
+                                         (VARIANT && a.rule == ADACOMP_RULE_PRINTED_COMPARE);
+                    const bool sent = nonzero && (mb[j][c] >= gm);
                     f |= sent ? (1u << c) : 0u;
                 }
             }
@@ -698,9 +711,16 @@ int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(a.n_tiles * a.fused_count), wg(kWG);
-    if (jcode == 0) hipLaunchKernelGGL(k_fused<4>, grid, wg, 0, s, a);
-    else if (jcode == 1) hipLaunchKernelGGL(k_fused<8>, grid, wg, 0, s, a);
-    else hipLaunchKernelGGL(k_fused<16>, grid, wg, 0, s, a);
+    const bool variant = a.rule != ADACOMP_RULE_ADACOMP || a.soft_factor_minus_1 != 1.0f;
+    if (!variant) {
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false>), grid, wg, 0, s, a);
+        else if (jcode == 1) hipLaunchKernelGGL((k_fused<8, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<16, false>), grid, wg, 0, s, a);
+    } else {
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, true>), grid, wg, 0, s, a);
+        else if (jcode == 1) hipLaunchKernelGGL((k_fused<8, true>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<16, true>), grid, wg, 0, s, a);
+    }
     return check_launch();
 }
 

@@ -116,6 +116,8 @@ struct CompressArgs {
     uint32_t o_tile_out, o_layer_nsel, o_layer_scale, o_gmax, o_chunk_rel;
     uint32_t n_tiles, n_layers, n_learners, keep_gmax;
     uint32_t fused_first, fused_count;  // learners covered by one k_fused launch
+    uint32_t rule;                      // ADACOMP_RULE_*
+    float soft_factor_minus_1;          // 1 for the paper's factor 2
     uint64_t o_stage;
     uint64_t capacity;        // bytes available in each packet buffer
     uint64_t fixed_bytes;

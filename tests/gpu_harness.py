@@ -50,12 +50,16 @@ class GpuSide:
         torch.cuda.synchronize()
         return self.packets[k].cpu().numpy()
 
-    def compress_batch(self, grads_np):
-        """One adacomp_compress_batch call over all learners; returns their packet buffers."""
+    def compress_batch(self, grads_np, rule=0, soft_factor=2.0):
+        """One adacomp_compress_batch (or _variant) call over all learners; returns their packet buffers."""
         g = [torch.from_numpy(x).to(DEV) for x in grads_np]
         for p in self.packets:
             p.fill_(POISON)
-        A.adacomp_compress_batch(self.table, g, self.residue, self.packets, self.ws, packet_capacity=self.capacity)
+        if rule == 0 and soft_factor == 2.0:
+            A.adacomp_compress_batch(self.table, g, self.residue, self.packets, self.ws, packet_capacity=self.capacity)
+        else:
+            A.adacomp_compress_variant(self.table, g, self.residue, self.packets, self.ws, rule=rule,
+                                       soft_factor=soft_factor, packet_capacity=self.capacity)
         torch.cuda.synchronize()
         return [p.cpu().numpy() for p in self.packets]
 
@@ -118,10 +122,11 @@ def compare_residue(got, want, mask, scale_hint, tag):
 
 
 def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, grads=None,
-               check_gmax=True, unpack_every_step=True, threads=8, label=None, batch=False):
+               check_gmax=True, unpack_every_step=True, threads=8, label=None, batch=False, rule=0, soft_factor=2.0):
     """Free-running (default) or step-locked comparison of GPU and oracle over several steps.
     grads: optional callable (learner, step) -> numpy float32 array overriding the generator."""
     label = label or wl.name
+    assert batch or (rule == 0 and soft_factor == 2.0), "variants go through the batched entry point"
     table, n_total = wl.table(), wl.n_total
     mask = layer_mask(table, n_total)
     gpu = GpuSide(table, n_total, n_learners, batch=batch)
@@ -137,7 +142,7 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
                 if step_locked:
                     for k in range(n_learners):
                         gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
-                batch_bufs = gpu.compress_batch(all_g)
+                batch_bufs = gpu.compress_batch(all_g, rule, soft_factor)
             for k in range(n_learners):
                 tag = f"{label} step {t} learner {k}"
                 say(tag)
@@ -145,7 +150,7 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
                 if step_locked and not batch:
                     gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
                 R_before = R_cpu[k].copy() if check_gmax else None
-                want = oracle_lib.compress(table, g, R_cpu[k])
+                want = oracle_lib.compress(table, g, R_cpu[k], rule=rule, soft_factor=soft_factor)
                 got_buf = batch_bufs[k] if batch else gpu.compress(k, g)
                 if check_gmax:
                     G = R_before + g

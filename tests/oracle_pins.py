@@ -404,4 +404,39 @@ def pin_variant_rules(o):
     assert np.flatnonzero(ls["selected"]).tolist() == [1, 6, 8, 13]
 
 
+def pin_soft_threshold_factor(o):
+    """Other soft-threshold factors (the paper studied 1.5 - 3.0 and chose 2): the operand is
+    residue + f dW.  With residue = 0 and dyadic gradients everything is exact, so the sent set is
+    {f |dW| >= bin max |dW|}; f = 1 adds nothing to local selection; f = 2 is the default path;
+    for random inputs H equals numpy's float32 G + (f - 1) * dW bit for bit."""
+    import oracle as om
+    n, T = 4000, 50
+    dW = (np.round(_rand(91, n) * 64) / 64).astype(f32)
+    gm = _binmax(dW, T)[np.arange(n) // T]
+    for f in (1.5, 3.0, 2.0):
+        r = o.pack_layer(np.zeros(n, f32), dW, T, soft_factor=f)
+        expect = (np.abs(dW.astype(np.float64)) * f >= gm) & (dW != 0)
+        assert np.array_equal(r["selected"], expect), f
+    counts = [o.pack_layer(np.zeros(n, f32), dW, T, soft_factor=f)["n_selected"] for f in (1.0, 1.5, 2.0, 3.0)]
+    assert counts == sorted(counts) and counts[0] < counts[-1]      # a larger factor sends more here
+    R, g = _rand(92, n), _rand(93, n, 0.4)
+    base = o.pack_layer(R, g, T)
+    same = o.pack_layer(R, g, T, soft_factor=2.0)
+    assert np.array_equal(base["H"], same["H"]) and np.array_equal(base["selected"], same["selected"])
+    one = o.pack_layer(R, g, T, soft_factor=1.0)
+    ls = o.pack_layer(R, g, T, rule=om.RULE_LS)
+    assert np.array_equal(one["selected"], ls["selected"]) and np.array_equal(one["residue"], ls["residue"])
+    for f in (1.5, 2.5, 3.0):
+        r = o.pack_layer(R, g, T, soft_factor=f)
+        G = R + g
+        assert np.array_equal(r["H"], G + f32(f - 1.0) * g)
+        assert np.array_equal(r["G"], G) and np.array_equal(r["gmax"], _binmax(G, T))   # the threshold does not move
+    for bad in (0.5, 17.0, float("nan")):
+        try:
+            o.pack_layer(R, g, T, soft_factor=bad)
+            raise AssertionError("factor outside 1..16 accepted")
+        except ValueError:
+            pass
+
+
 PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

@@ -211,6 +211,57 @@ def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
         gpu.close()
 
 
+# ------------------------------------------------------------------------------------------------
+# selection variants: the printed compare alone, local selection, other soft-threshold factors
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("rule,factor", [(1, 2.0), (2, 2.0), (0, 1.5), (0, 3.0), (0, 1.0), (1, 2.5), (0, 2.75)])
+def test_variants_workload2(H, oracle_lib, rule, factor):
+    wl = W.workload(2)
+    stats = H.run_parity(oracle_lib, wl, 2, 5, batch=True, rule=rule, soft_factor=factor,
+                         label=f"variant rule {rule} factor {factor}")
+    assert all(s[2] > 0 for s in stats)
+
+
+@pytest.mark.parametrize("rule,factor", [(1, 2.0), (2, 2.0), (0, 1.5)])
+def test_variants_edge_tables_with_zeros(H, oracle_lib, rule, factor):
+    """Zero stretches and ties: the printed compare sends the zeros of an all-zero bin."""
+    wl = W.custom("varz", [("a", 50 * 90 + 11, 50), ("b", 500 * 21 + 3, 500), ("c", 64 * 3 + 1, 64), ("d", 5000, 4097)])
+    n = wl.n_total
+
+    def grads(k, t):
+        g = np.round(_rand(300 * k + t, n) * 2).astype(f32) / 4
+        g[(np.arange(n) // 700) % 3 == 0] = 0
+        return g
+    H.run_parity(oracle_lib, wl, 2, 4, grads=grads, batch=True, rule=rule, soft_factor=factor, label="variant zeros")
+
+
+def test_variant_default_equals_compress(H):
+    """rule 0 with factor 2 through the variant entry point is adacomp_compress bit for bit, and bad
+    rules / factors are refused."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(1)
+    table, n = wl.table(), wl.n_total
+    a, b = G.GpuSide(table, n, 1), G.GpuSide(table, n, 1, batch=True)
+    try:
+        for t in range(3):
+            g = W.gradient(wl, 0, t)
+            pa = a.compress(0, g)
+            gt = torch.from_numpy(g).to(G.DEV)
+            b.packets[0].fill_(G.POISON)
+            A.adacomp_compress_variant(table, [gt], b.residue, b.packets, b.ws, rule=0, soft_factor=2.0)
+            torch.cuda.synchronize()
+            assert np.array_equal(pa, b.packets[0].cpu().numpy())
+            assert torch.equal(a.residue[0], b.residue[0])
+        for rule, factor in [(3, 2.0), (0, 0.5), (0, 17.0), (0, float("nan"))]:
+            with pytest.raises(A.AdacompError) as e:
+                A.adacomp_compress_variant(table, [gt], b.residue, b.packets, b.ws, rule=rule, soft_factor=factor)
+            assert e.value.code == -1
+    finally:
+        a.close()
+        b.close()
+
+
 def test_ties_and_zeros(H, oracle_lib):
     """Coarse dyadic grid: many equal magnitudes, exact cancellations to +-0, all-zero bins."""
     wl = W.custom("ties", [("a", 50 * 300 + 11, 50), ("b", 500 * 40 + 3, 500)])

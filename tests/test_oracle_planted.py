@@ -18,6 +18,8 @@ MUTANTS = {
     "G_minus_dW": ("G[index] = residue_in[index] + dW[index];", "G[index] = residue_in[index] - dW[index];"),
     "H_minus_dW": ("H[index] = G[index] + dW[index];", "H[index] = G[index] - dW[index];"),
     "H_from_residue_once": ("H[index] = G[index] + dW[index];", "H[index] = residue_in[index] + 2.0f * dW[index];"),
+    "factor_not_reduced_by_one": ("float f_minus_1 = soft_factor - 1.0f;", "float f_minus_1 = soft_factor;"),
+    "factor_applied_to_G": ("float extra = f_minus_1 * dW[index];", "float extra = f_minus_1 * G[index];"),
     "gmax_from_H": ("float a = fabsf(G[index]);", "float a = fabsf(H[index]);"),
     "gmax_signed": ("float a = fabsf(G[index]);", "float a = G[index];"),
     "bin_end_off_by_one": ("uint64_t lo = i * T, hi = lo + T < n ? lo + T : n;\n        float m = 0.0f;",
