@@ -205,6 +205,30 @@ def main():
     step_alg_bytes = n_learners * (12 * n_params + packet_bytes_mean) + 4 * n_params + n_learners * packet_bytes_mean
     step_frac = step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
+    # ---- the follow-on row: unpack + average + optimizer step in one pass (not part of `value`) -------
+    upd = {}
+    try:
+        wts = torch.zeros(n_total, dtype=torch.float32, device=dev)
+        st1 = torch.zeros(n_total, dtype=torch.float32, device=dev)
+        st2 = torch.zeros(n_total, dtype=torch.float32, device=dev)
+        for name, kind, st2_arg, bytes_per_elem in (("sgd_momentum", binding.OPT_SGD_MOMENTUM, None, 16),
+                                                    ("adam", binding.OPT_ADAM, st2, 24)):
+            A.adacomp_unpack_update(table, packets, None, wts, st1, st2_arg, ws, kind, 1e-3, momentum=0.9,
+                                    bias1=0.1, bias2=0.001)
+            u0, u1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            u0.record()
+            for _ in range(5):
+                A.adacomp_unpack_update(table, packets, None, wts, st1, st2_arg, ws, kind, 1e-3, momentum=0.9,
+                                        bias1=0.1, bias2=0.001)
+            u1.record()
+            torch.cuda.synchronize()
+            ms = u0.elapsed_time(u1) / 5
+            upd[name] = {"ms": round(ms, 4), "algorithmic_bytes_per_elem": bytes_per_elem,
+                         "hbm_frac": round(bytes_per_elem * n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del wts, st1, st2
+    except Exception as e:  # the main line must not depend on this leg
+        upd = {"error": str(e)}
+
     # ---- CPU oracle on a bounded sample ----------------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -239,6 +263,7 @@ def main():
         "cpu_baseline": cpu,
         "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),
         "compress_ms_per_step": round(compress_ms, 4), "unpack_ms_per_step": round(unpack_ms, 4),
+        "unpack_update": upd,
         "compression": {"paper_accounting": round(ratio_paper, 2), "wire": round(ratio_wire, 2),
                         "selected_per_learner_last_step": n_sel // n_learners,
                         "packet_bytes_mean_last_step": int(packet_bytes_mean),

@@ -184,6 +184,34 @@ int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
                               const void *const *packets, uint32_t n_learners, float *dense_out,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---- unpack() + averageGradients() + updateWeights() in one pass (Algorithm 1, last three steps) */
+
+#define ADACOMP_OPT_SGD_MOMENTUM 1u /* v <- momentum v + g;  w <- w - lr v                                  */
+#define ADACOMP_OPT_ADAM 2u         /* m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+                                       w <- w - lr (m / bias1) / (sqrt(v / bias2) + eps)                    */
+typedef struct {
+    uint32_t kind;  /* ADACOMP_OPT_* */
+    float lr;
+    float momentum; /* SGD */
+    float beta1, beta2, eps;
+    float bias1, bias2; /* Adam's 1 - beta1^t and 1 - beta2^t for this step, computed by the caller */
+} adacomp_optimizer_t;
+
+/* Like adacomp_unpack_accumulate, then g = sum / n_learners ("Average among all learners") and one
+ * optimizer step on the weights ("Performed locally at each learner"), without writing the dense
+ * gradient to memory and reading it back.  The paper trains with SGD with momentum 0.9 and with
+ * Adam (sections "Experiment Results", "Robustness of the AdaComp Technique") and leaves the
+ * update rule to the framework; the forms above are the usual ones, each arithmetic operation a
+ * separate float32 operation in the order written.
+ * dense_out  may be NULL (the sum is then never stored) unless n_learners > 64; if given it
+ *            receives the un-averaged sum as in adacomp_unpack_accumulate.
+ * weights, state1 (momentum buffer, or Adam's m), state2 (Adam's v; NULL for SGD): float32 buffers
+ *            laid out like the gradient, 16-byte aligned, updated in place on every layer element.
+ * n_learners must be >= 1. */
+int adacomp_unpack_update(const adacomp_layer_t *layers, uint32_t n_layers, const void *const *packets,
+                          uint32_t n_learners, float *dense_out, float *weights, float *state1, float *state2,
+                          const adacomp_optimizer_t *opt, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---- diagnostics ---------------------------------------------------------------------------- */
 
 const char *adacomp_strerror(int code);

@@ -61,6 +61,13 @@ class Oracle:
         L.adacomp_oracle_unpack_accumulate.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32,
                                                        ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32, fp]
 
+        cf = ctypes.c_float
+        L.adacomp_oracle_update_sgd.restype = ctypes.c_int
+        L.adacomp_oracle_update_sgd.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32, fp, ctypes.c_uint32, fp, fp, cf, cf]
+        L.adacomp_oracle_update_adam.restype = ctypes.c_int
+        L.adacomp_oracle_update_adam.argtypes = [ctypes.POINTER(_Layer), ctypes.c_uint32, fp, ctypes.c_uint32, fp, fp, fp,
+                                                 cf, cf, cf, cf, cf, cf]
+
     @staticmethod
     def _f(a):
         assert a.dtype == np.float32 and a.flags.c_contiguous
@@ -117,6 +124,22 @@ class Oracle:
         if rc != 0:
             raise OracleError(rc)
         return dense
+
+
+    def update_sgd(self, layers, dense_sum, n_learners, weights, momentum_buf, lr, momentum):
+        """averageGradients + SGD-with-momentum step, in place on weights and momentum_buf."""
+        rc = self.lib.adacomp_oracle_update_sgd(_layer_array(layers), len(layers), self._f(dense_sum), n_learners,
+                                                self._f(weights), self._f(momentum_buf), lr, momentum)
+        if rc != 0:
+            raise OracleError(rc)
+
+    def update_adam(self, layers, dense_sum, n_learners, weights, m_buf, v_buf, lr, beta1, beta2, eps, bias1, bias2):
+        """averageGradients + Adam step, in place on weights, m_buf and v_buf."""
+        rc = self.lib.adacomp_oracle_update_adam(_layer_array(layers), len(layers), self._f(dense_sum), n_learners,
+                                                 self._f(weights), self._f(m_buf), self._f(v_buf), lr, beta1, beta2,
+                                                 eps, bias1, bias2)
+        if rc != 0:
+            raise OracleError(rc)
 
 
 class OracleError(RuntimeError):

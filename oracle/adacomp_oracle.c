@@ -323,3 +323,55 @@ int adacomp_oracle_unpack_accumulate(const adacomp_oracle_layer_t *layers, uint3
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * averageGradients() and updateWeights() of Algorithm 1, applied to the dense sum unpack() made.
+ * Every operation is a separate float operation in the order written (no fused multiply-add).
+ * ---------------------------------------------------------------------------------------- */
+int adacomp_oracle_update_sgd(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
+                              const float *dense_sum, uint32_t n_learners, float *weights,
+                              float *momentum_buf, float lr, float momentum)
+{
+    if (check_layers(layers, n_layers) != 0 || !dense_sum || !weights || !momentum_buf || n_learners == 0) return -1;
+    float n = (float)n_learners;
+    for (uint32_t l = 0; l < n_layers; ++l)
+        for (uint64_t e = 0; e < layers[l].n_elems; ++e) {
+            uint64_t i = layers[l].elem_offset + e;
+            float g = dense_sum[i] / n;      /* average among all learners */
+            float mv = momentum * momentum_buf[i];
+            float v = mv + g;                /* v <- momentum * v + g      */
+            momentum_buf[i] = v;
+            float step = lr * v;
+            weights[i] = weights[i] - step;  /* w <- w - lr * v            */
+        }
+    return 0;
+}
+
+int adacomp_oracle_update_adam(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
+                               const float *dense_sum, uint32_t n_learners, float *weights, float *m_buf,
+                               float *v_buf, float lr, float beta1, float beta2, float eps,
+                               float bias1, float bias2)
+{
+    if (check_layers(layers, n_layers) != 0 || !dense_sum || !weights || !m_buf || !v_buf || n_learners == 0) return -1;
+    float n = (float)n_learners;
+    float one_minus_b1 = 1.0f - beta1, one_minus_b2 = 1.0f - beta2;
+    for (uint32_t l = 0; l < n_layers; ++l)
+        for (uint64_t e = 0; e < layers[l].n_elems; ++e) {
+            uint64_t i = layers[l].elem_offset + e;
+            float g = dense_sum[i] / n;                 /* average among all learners          */
+            float a = beta1 * m_buf[i], b = one_minus_b1 * g;
+            float m = a + b;                            /* m <- beta1 m + (1 - beta1) g        */
+            float g2 = g * g;
+            float c = beta2 * v_buf[i], d = one_minus_b2 * g2;
+            float v = c + d;                            /* v <- beta2 v + (1 - beta2) g^2      */
+            m_buf[i] = m;
+            v_buf[i] = v;
+            float m_hat = m / bias1;                    /* bias1 = 1 - beta1^t                 */
+            float v_hat = v / bias2;                    /* bias2 = 1 - beta2^t                 */
+            float denom = sqrtf(v_hat) + eps;
+            float ratio = m_hat / denom;
+            float step = lr * ratio;
+            weights[i] = weights[i] - step;             /* w <- w - lr m_hat / (sqrt(v_hat)+eps) */
+        }
+    return 0;
+}

@@ -18,7 +18,8 @@
  *   - Section "Experiment Results": 8-bit sparse-index words for L_T < 64 (here: <= 64, index
  *     0..63 fits 6 bits), 16-bit words up to L_T = 16K, 2 bits of each word hold the ternary value.
  *   - Algorithm 1: unpack() then averageGradients() are separate steps; unpack here produces the
- *     plain sum over learners.
+ *     plain sum over learners; averageGradients() and updateWeights() follow as update_sgd /
+ *     update_adam.
  *
  * Readings taken where the paper is silent or at odds with itself:
  *   union rule      an element is sent when G != 0 and (|H| >= g_max or |G| >= g_max), so the bin
@@ -103,6 +104,21 @@ long long adacomp_oracle_compress(const adacomp_oracle_layer_t *layers, uint32_t
 int adacomp_oracle_unpack_accumulate(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
                                      const void *const *packets, uint32_t n_learners,
                                      float *dense_out);
+
+/* averageGradients() then updateWeights() (Algorithm 1) on the dense sum of n_learners decoded
+ * packets.  The paper trains with "SGD with momentum (=0.9)" and with Adam and leaves the update
+ * rule to the framework; the forms taken here are the usual ones:
+ *   SGD     g = sum / n;  v <- momentum * v + g;  w <- w - lr * v
+ *   Adam    g = sum / n;  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *           w <- w - lr * (m / bias1) / (sqrt(v / bias2) + eps),  bias_k = 1 - beta_k^t passed in
+ * Each arithmetic operation is one float operation, in that order.  Returns 0 or -1. */
+int adacomp_oracle_update_sgd(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
+                              const float *dense_sum, uint32_t n_learners, float *weights,
+                              float *momentum_buf, float lr, float momentum);
+int adacomp_oracle_update_adam(const adacomp_oracle_layer_t *layers, uint32_t n_layers,
+                               const float *dense_sum, uint32_t n_learners, float *weights, float *m_buf,
+                               float *v_buf, float lr, float beta1, float beta2, float eps,
+                               float bias1, float bias2);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ EXPORTS = [
     "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
     "adacomp_workspace_bytes_batch", "adacomp_workspace_init", "adacomp_workspace_release",
     "adacomp_compress", "adacomp_compress_batch", "adacomp_compress_variant",
-    "adacomp_unpack_accumulate", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
+    "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
     "adacomp_selftest_binindex", "adacomp_timing_enable", "adacomp_timing_read",
 ]
@@ -35,6 +35,15 @@ PACKET_LAYER = np.dtype([("elem_offset", "<u8"), ("n_elems", "<u8"), ("L_T", "<u
 class Layer(ctypes.Structure):
     _fields_ = [("elem_offset", ctypes.c_uint64), ("n_elems", ctypes.c_uint64),
                 ("L_T", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class Optimizer(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_uint32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("bias1", ctypes.c_float), ("bias2", ctypes.c_float)]
+
+
+OPT_SGD_MOMENTUM, OPT_ADAM = 1, 2
 
 
 class AdacompError(RuntimeError):
@@ -68,6 +77,8 @@ def lib():
         L.adacomp_workspace_release.argtypes = [vp]
         L.adacomp_compress.argtypes = [LP, u32, vp, vp, vp, sz, vp, sz, vp]
         L.adacomp_unpack_accumulate.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, sz, vp]
+        L.adacomp_unpack_update.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, vp, vp,
+                                            ctypes.POINTER(Optimizer), vp, sz, vp]
         L.adacomp_strerror.restype = ctypes.c_char_p
         L.adacomp_strerror.argtypes = [ctypes.c_int]
         L.adacomp_workspace_gmax.argtypes = [LP, u32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
@@ -170,6 +181,19 @@ def adacomp_unpack_accumulate(layers, packets, dense_out, workspace):
     _check(lib().adacomp_unpack_accumulate(layer_array(layers), len(layers), ptrs, len(packets),
                                            _ptr(dense_out), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_unpack_update(layers, packets, dense_out, weights, state1, state2, workspace, kind, lr, momentum=0.0,
+                          beta1=0.9, beta2=0.999, eps=1e-8, bias1=1.0, bias2=1.0):
+    """unpack + average + one optimizer step; dense_out and state2 may be None."""
+    ptrs = (ctypes.c_void_p * max(1, len(packets)))(*[p.data_ptr() for p in packets])
+    opt = Optimizer(int(kind), lr, momentum, beta1, beta2, eps, bias1, bias2)
+    null = ctypes.c_void_p(None)
+    _check(lib().adacomp_unpack_update(layer_array(layers), len(layers), ptrs, len(packets),
+                                       _ptr(dense_out) if dense_out is not None else null, _ptr(weights),
+                                       _ptr(state1), _ptr(state2) if state2 is not None else null,
+                                       ctypes.byref(opt), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()))
 
 
 def adacomp_workspace_gmax(layers):

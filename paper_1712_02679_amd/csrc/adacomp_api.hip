@@ -413,11 +413,11 @@ int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const flo
                                   workspace, workspace_bytes, hip_stream);
 }
 
-int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
-                              const void *const *packets, uint32_t n_learners, float *dense_out,
-                              void *workspace, size_t workspace_bytes, void *hip_stream)
+static int unpack_common(const adacomp_layer_t *layers, uint32_t n_layers, const void *const *packets,
+                         uint32_t n_learners, float *dense_out, float *weights, float *state1, float *state2,
+                         const adacomp_optimizer_t *opt, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!dense_out || (n_learners > 0 && !packets)) return ADACOMP_EINVAL;
+    if (n_learners > 0 && !packets) return ADACOMP_EINVAL;
     if (reinterpret_cast<uintptr_t>(dense_out) % 16) return ADACOMP_EALIGN;
     for (uint32_t k = 0; k < n_learners; ++k) {
         if (!packets[k]) return ADACOMP_EINVAL;
@@ -434,17 +434,61 @@ int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
     a.dense = dense_out;
     a.n_tiles = p.n_utiles;
     a.n_layers = p.n_layers;
+    a.weights = weights; a.state1 = state1; a.state2 = state2;
+    a.n_average = float(n_learners);
+    a.lr = a.p1 = a.p2 = a.one_minus_p1 = a.one_minus_p2 = a.eps = 0.f;
+    a.bias1 = a.bias2 = 1.f;
+    if (opt) {
+        a.lr = opt->lr;
+        if (opt->kind == ADACOMP_OPT_SGD_MOMENTUM) a.p1 = opt->momentum;
+        else {
+            a.p1 = opt->beta1; a.p2 = opt->beta2;
+            a.one_minus_p1 = 1.0f - opt->beta1; a.one_minus_p2 = 1.0f - opt->beta2;
+            a.eps = opt->eps; a.bias1 = opt->bias1; a.bias2 = opt->bias2;
+        }
+    }
     uint32_t done = 0;
-    do {  // 64 learners per launch; later launches add onto the stored partial sum, same order
+    do {  // 64 learners per launch; later launches add onto the stored partial sum, same order;
+          // the update is applied by the last launch, when the sum is complete
         const uint32_t now = std::min(n_learners - done, kMaxPacketArgs);
+        const bool last = done + now == n_learners;
         a.n_learners = now;
         a.accumulate = done > 0;
+        a.mode = (opt && last) ? opt->kind : 0u;
+        a.write_dense = dense_out != nullptr;
         for (uint32_t k = 0; k < kMaxPacketArgs; ++k)
             a.packets[k] = k < now ? static_cast<const uint8_t *>(packets[done + k]) : nullptr;
         if ((rc = launch_unpack(a, hip_stream)) != ADACOMP_OK) return rc;
         done += now;
     } while (done < n_learners);
     return ADACOMP_OK;
+}
+
+int adacomp_unpack_accumulate(const adacomp_layer_t *layers, uint32_t n_layers,
+                              const void *const *packets, uint32_t n_learners, float *dense_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!dense_out) return ADACOMP_EINVAL;
+    return unpack_common(layers, n_layers, packets, n_learners, dense_out, nullptr, nullptr, nullptr, nullptr,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int adacomp_unpack_update(const adacomp_layer_t *layers, uint32_t n_layers, const void *const *packets,
+                          uint32_t n_learners, float *dense_out, float *weights, float *state1, float *state2,
+                          const adacomp_optimizer_t *opt, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!opt || !weights || !state1 || n_learners == 0) return ADACOMP_EINVAL;
+    if (opt->kind != ADACOMP_OPT_SGD_MOMENTUM && opt->kind != ADACOMP_OPT_ADAM) return ADACOMP_EINVAL;
+    if (opt->kind == ADACOMP_OPT_ADAM && (!state2 || !(opt->bias1 > 0.f) || !(opt->bias2 > 0.f))) return ADACOMP_EINVAL;
+    if (!dense_out && n_learners > kMaxPacketArgs) return ADACOMP_EINVAL;  // the partial sums need a home
+    if (reinterpret_cast<uintptr_t>(weights) % 16 || reinterpret_cast<uintptr_t>(state1) % 16 ||
+        reinterpret_cast<uintptr_t>(state2) % 16)
+        return ADACOMP_EALIGN;
+    if (weights == state1 || weights == state2 || state1 == state2 || dense_out == weights || dense_out == state1 ||
+        (dense_out && dense_out == state2))
+        return ADACOMP_EINVAL;
+    return unpack_common(layers, n_layers, packets, n_learners, dense_out, weights, state1, state2, opt, workspace,
+                         workspace_bytes, hip_stream);
 }
 
 const char *adacomp_strerror(int code)

@@ -644,6 +644,38 @@ __device__ __forceinline__ void unpack_tile(const UnpackArgs &a, const UTileDev 
     }
 }
 
+// averageGradients() and updateWeights() of Algorithm 1 on one element of the finished sum: every
+// operation is a separate float32 operation (contraction is off), division and square root are
+// the correctly rounded ones.
+template <int MODE>
+__device__ __forceinline__ void apply_update(const UnpackArgs &a, float sum, float &w, float &s1, float &s2)
+{
+    const float g = sum / a.n_average;
+    if (MODE == 1) {  // SGD with momentum: v <- mu v + g; w <- w - lr v
+        const float mv = a.p1 * s1;
+        const float v = mv + g;
+        s1 = v;
+        const float step = a.lr * v;
+        w = w - step;
+    } else {          // Adam
+        const float m1 = a.p1 * s1, m2 = a.one_minus_p1 * g;
+        const float m = m1 + m2;
+        const float g2 = g * g;
+        const float v1 = a.p2 * s2, v2 = a.one_minus_p2 * g2;
+        const float v = v1 + v2;
+        s1 = m;
+        s2 = v;
+        const float m_hat = m / a.bias1;
+        const float v_hat = v / a.bias2;
+        const float denom = sqrtf(v_hat) + a.eps;
+        const float ratio = m_hat / denom;
+        const float step = a.lr * ratio;
+        w = w - step;
+    }
+}
+
+// MODE 0: dense_out <- sum.  MODE 1 / 2: also (or only) the SGD / Adam step on weights and state.
+template <int MODE>
 __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 {
     const uint32_t tile = blockIdx.x;
@@ -682,12 +714,38 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
         const float4 v = *reinterpret_cast<const float4 *>(&s_acc[i]);
-        if (vec && i + 4u <= n) store_stream4(out + i, vfloat4{v.x, v.y, v.z, v.w});
-        else {
-            out[i] = v.x;
-            if (i + 1u < n) out[i + 1] = v.y;
-            if (i + 2u < n) out[i + 2] = v.z;
-            if (i + 3u < n) out[i + 3] = v.w;
+        const bool full = vec && i + 4u <= n;
+        if (a.write_dense) {
+            if (full) store_stream4(out + i, vfloat4{v.x, v.y, v.z, v.w});
+            else {
+                out[i] = v.x;
+                if (i + 1u < n) out[i + 1] = v.y;
+                if (i + 2u < n) out[i + 2] = v.z;
+                if (i + 3u < n) out[i + 3] = v.w;
+            }
+        }
+        if (MODE != 0) {
+            float *__restrict__ wp = a.weights + ut.elem_base + i;
+            float *__restrict__ p1 = a.state1 + ut.elem_base + i;
+            float *__restrict__ p2 = MODE == 2 ? a.state2 + ut.elem_base + i : nullptr;
+            const float sum[4] = {v.x, v.y, v.z, v.w};
+            if (full) {
+                vfloat4 w4 = load_stream4(wp), s14 = load_stream4(p1), s24 = MODE == 2 ? load_stream4(p2) : vfloat4{0.f, 0.f, 0.f, 0.f};
+                float w[4] = {w4.x, w4.y, w4.z, w4.w}, s1[4] = {s14.x, s14.y, s14.z, s14.w}, s2[4] = {s24.x, s24.y, s24.z, s24.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) apply_update<MODE>(a, sum[c], w[c], s1[c], s2[c]);
+                store_stream4(wp, vfloat4{w[0], w[1], w[2], w[3]});
+                store_stream4(p1, vfloat4{s1[0], s1[1], s1[2], s1[3]});
+                if (MODE == 2) store_stream4(p2, vfloat4{s2[0], s2[1], s2[2], s2[3]});
+            } else {
+                for (uint32_t c = 0; c < 4u && i + c < n; ++c) {
+                    float w = wp[c], s1 = p1[c], s2 = MODE == 2 ? p2[c] : 0.f;
+                    apply_update<MODE>(a, sum[c], w, s1, s2);
+                    wp[c] = w;
+                    p1[c] = s1;
+                    if (MODE == 2) p2[c] = s2;
+                }
+            }
         }
     }
 }
@@ -738,7 +796,10 @@ int launch_place(const CompressArgs &a, void *stream)
 
 int launch_unpack(const UnpackArgs &a, void *stream)
 {
-    hipLaunchKernelGGL(k_unpack, dim3(a.n_tiles), dim3(kWG), 0, static_cast<hipStream_t>(stream), a);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (a.mode == 1) hipLaunchKernelGGL(k_unpack<1>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    else if (a.mode == 2) hipLaunchKernelGGL(k_unpack<2>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    else hipLaunchKernelGGL(k_unpack<0>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
     return check_launch();
 }
 

@@ -131,6 +131,11 @@ struct UnpackArgs {
     const LayerDev *layers;
     float *dense;
     uint32_t n_tiles, n_layers, n_learners, accumulate;
+    uint32_t write_dense;              // 0: the sum is only consumed by the update
+    uint32_t mode;                     // 0: sum only; 1: SGD with momentum; 2: Adam (applied by this launch)
+    float *weights, *state1, *state2;  // momentum buffer, or Adam's m and v
+    float n_average;                   // learner count the sum is divided by
+    float lr, p1, p2, one_minus_p1, one_minus_p2, eps, bias1, bias2;
     const uint8_t *packets[kMaxPacketArgs];
 };
 

@@ -439,4 +439,77 @@ def pin_soft_threshold_factor(o):
             pass
 
 
+def pin_update_sgd(o):
+    """averageGradients + SGD with momentum: closed forms.  lr = 0 leaves the weights alone; with
+    momentum 0 the step is lr * sum / n; a constant gradient builds the geometric series
+    v_k = g (1 - mu^k) / (1 - mu); elements outside the layers are untouched."""
+    table = [(0, 1001, 50), (1004, 700, 500)]
+    n = 1704
+    mask = np.zeros(n, bool)
+    mask[:1001] = True
+    mask[1004:] = True
+    s = _rand(101, n)
+    w0 = _rand(102, n)
+    w, v = w0.copy(), np.zeros(n, f32)
+    o.update_sgd(table, s, 4, w, v, 0.0, 0.9)
+    assert np.array_equal(w[mask], w0[mask]) and np.array_equal(v[mask], s[mask] / f32(4))
+    assert np.all(v[~mask] == 0) and np.array_equal(w[~mask], w0[~mask])
+    w, v = w0.copy(), np.zeros(n, f32)
+    o.update_sgd(table, s, 8, w, v, 0.5, 0.0)             # all dyadic factors: exact
+    assert np.array_equal(w[mask], (w0 - f32(0.5) * (s / f32(8)))[mask])
+    # geometric series with dyadic numbers (mu = 0.5, g = 1): v_k = 2 - 2^(1-k) exactly
+    ones = np.ones(n, f32) * f32(3)
+    w, v = np.zeros(n, f32), np.zeros(n, f32)
+    for k in range(1, 11):
+        o.update_sgd(table, ones, 3, w, v, 0.25, 0.5)
+        assert np.all(v[mask] == f32(2.0 - 2.0 ** (1 - k)))
+    assert np.all(w[mask] == f32(-0.25 * sum(2.0 - 2.0 ** (1 - k) for k in range(1, 11))))
+    # general values: the same sequence of float32 operations in numpy
+    w, v = w0.copy(), _rand(103, n)
+    v0 = v.copy()
+    o.update_sgd(table, s, 7, w, v, 0.01, 0.9)
+    g = s / f32(7)
+    v_ref = f32(0.9) * v0 + g
+    assert np.array_equal(v[mask], v_ref[mask]) and np.array_equal(w[mask], (w0 - f32(0.01) * v_ref)[mask])
+
+
+def pin_update_adam(o):
+    """averageGradients + Adam: from zero state at t = 1, m_hat = g and v_hat = g^2, so the first
+    step is lr * g / (|g| + eps): magnitude lr (to within eps / |g|), sign of g, whatever the
+    gradient's size (the scale invariance of Adam); a zero gradient moves nothing."""
+    table = [(0, 900, 50)]
+    n = 900
+    g4 = _rand(111, n) * f32(10.0) ** np.random.default_rng(5).integers(-3, 3, n).astype(f32)
+    g4[::50] = 0
+    lr, b1, b2, eps = 1e-3, 0.9, 0.999, 1e-8
+    w, m, v = np.zeros(n, f32), np.zeros(n, f32), np.zeros(n, f32)
+    o.update_adam(table, g4 * f32(4), 4, w, m, v, lr, b1, b2, eps, 1 - b1, 1 - b2)
+    nz = g4 != 0
+    assert np.all(w[~nz] == 0) and np.all(m[~nz] == 0) and np.all(v[~nz] == 0)
+    assert np.all(np.sign(w[nz]) == -np.sign(g4[nz]))
+    a64 = np.abs(g4[nz].astype(np.float64))
+    assert np.allclose(np.abs(w[nz]), lr * a64 / (a64 + eps), rtol=1e-5)
+    assert np.all(np.abs(w[nz]) <= lr * (1 + 2e-5)) and np.median(np.abs(w[nz])) > 0.99 * lr
+    omb1, omb2 = float(f32(1) - f32(b1)), float(f32(1) - f32(b2))   # the one-minus-beta factors are float32
+    assert np.allclose(m[nz], omb1 * g4[nz].astype(np.float64), rtol=1e-6)
+    assert np.allclose(v[nz], omb2 * g4[nz].astype(np.float64) ** 2, rtol=1e-6)
+    # steady state with a constant gradient: m -> g, v -> g^2, step -> lr * sign(g)
+    w, m, v = np.zeros(n, f32), np.zeros(n, f32), np.zeros(n, f32)
+    for t in range(1, 60):
+        w_before = w.copy()
+        o.update_adam(table, g4, 1, w, m, v, lr, b1, b2, eps, 1 - b1 ** t, 1 - b2 ** t)
+    big = np.abs(g4) > 1e-4
+    assert np.allclose((w_before - w)[big], lr * np.sign(g4[big]), rtol=2e-3)
+    # general values: the same sequence of float32 operations in numpy (sqrt and divide are
+    # correctly rounded in both)
+    w0, m0, v0 = _rand(112, n), _rand(113, n, 0.1), np.abs(_rand(114, n, 0.01))
+    w, m, v = w0.copy(), m0.copy(), v0.copy()
+    o.update_adam(table, g4, 3, w, m, v, lr, b1, b2, eps, 0.19, 0.002)
+    g = g4 / f32(3)
+    m_ref = f32(b1) * m0 + (f32(1) - f32(b1)) * g
+    v_ref = f32(b2) * v0 + (f32(1) - f32(b2)) * (g * g)
+    w_ref = w0 - f32(lr) * ((m_ref / f32(0.19)) / (np.sqrt(v_ref / f32(0.002)) + f32(eps)))
+    assert np.array_equal(m, m_ref) and np.array_equal(v, v_ref) and np.array_equal(w, w_ref)
+
+
 PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

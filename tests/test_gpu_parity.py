@@ -262,6 +262,89 @@ def test_variant_default_equals_compress(H):
         b.close()
 
 
+# ------------------------------------------------------------------------------------------------
+# unpack + average + optimizer step in one pass
+# ------------------------------------------------------------------------------------------------
+def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0):
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    table, n = wl.table(), wl.n_total
+    mask = G.layer_mask(table, n)
+    gpu = G.GpuSide(table, n, n_learners, batch=True)
+    rng = np.random.default_rng(seed)
+    w_cpu = rng.standard_normal(n).astype(f32)
+    s1_cpu = np.zeros(n, f32)
+    s2_cpu = np.zeros(n, f32)
+    w_gpu, s1_gpu, s2_gpu = (torch.from_numpy(x.copy()).to(G.DEV) for x in (w_cpu, s1_cpu, s2_cpu))
+    R_cpu = [np.zeros(n, f32) for _ in range(n_learners)]
+    lr, mu, b1, b2, eps = 0.05, 0.9, 0.9, 0.999, 1e-8
+    try:
+        for t in range(n_steps):
+            G.say(f"{wl.name} update kind {kind} step {t}")
+            grads = [W.gradient(wl, k, t, seed=seed) for k in range(n_learners)]
+            gpu.compress_batch(grads)
+            pk_cpu = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(n_learners)]
+            dense_cpu = oracle_lib.unpack_accumulate(table, pk_cpu, n)
+            dense_cpu[~mask] = 0
+            bias1, bias2 = float(f32(1 - b1 ** (t + 1))), float(f32(1 - b2 ** (t + 1)))
+            if kind == 1:
+                oracle_lib.update_sgd(table, dense_cpu, n_learners, w_cpu, s1_cpu, lr, mu)
+            else:
+                oracle_lib.update_adam(table, dense_cpu, n_learners, w_cpu, s1_cpu, s2_cpu, lr, b1, b2, eps, bias1, bias2)
+            gpu.dense.fill_(float("nan"))
+            A.adacomp_unpack_update(table, gpu.packets, gpu.dense if with_dense else None, w_gpu, s1_gpu,
+                                    s2_gpu if kind == 2 else None, gpu.ws, kind, lr, momentum=mu, beta1=b1,
+                                    beta2=b2, eps=eps, bias1=bias1, bias2=bias2)
+            torch.cuda.synchronize()
+            for name, got, want in (("weights", w_gpu, w_cpu), ("state1", s1_gpu, s1_cpu), ("state2", s2_gpu, s2_cpu)):
+                got = got.cpu().numpy()
+                assert np.array_equal(got[~mask], want[~mask]), f"{name}: touched outside the layers"
+                if not np.array_equal(got[mask].view(np.uint32), want[mask].view(np.uint32)):
+                    rel = np.abs(got[mask].astype(np.float64) - want[mask]) / np.maximum(np.abs(want[mask]), 1e-30)
+                    raise AssertionError(f"{name} step {t}: not bit-equal, max relative difference {rel.max():.3e}")
+            if with_dense:
+                got = gpu.dense.cpu().numpy()
+                assert np.array_equal(got[mask].view(np.uint32), dense_cpu[mask].view(np.uint32))
+                assert np.isnan(got[~mask]).all()
+    finally:
+        gpu.close()
+
+
+@pytest.mark.parametrize("kind,with_dense", [(1, False), (1, True), (2, False), (2, True)])
+def test_unpack_update_workload2(H, oracle_lib, kind, with_dense):
+    _update_case(oracle_lib, W.workload(2), 4, 6, kind, with_dense)
+
+
+@pytest.mark.parametrize("kind", [1, 2])
+def test_unpack_update_edge_table(H, oracle_lib, kind):
+    wl = W.custom("upd_edge", EDGE_TABLES["mixed_with_gaps"] + [("z", 16383 * 2 + 7, 16383)], dist="normal_outliers")
+    _update_case(oracle_lib, wl, 3, 3, kind, False, seed=5)
+
+
+def test_unpack_update_many_learners_and_errors(H, oracle_lib):
+    """70 learners: two launches, the step is applied once by the last; dense_out is then required."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.custom("upd70", [("a", 50 * 40 + 7, 50), ("b", 500 * 12 + 11, 500)])
+    _update_case(oracle_lib, wl, 70, 2, 1, True, seed=2)
+    table, n = wl.table(), wl.n_total
+    gpu = G.GpuSide(table, n, 70, batch=True)
+    try:
+        w = torch.zeros(n, device=G.DEV)
+        s1 = torch.zeros(n, device=G.DEV)
+        with pytest.raises(A.AdacompError) as e:      # no dense_out with more than 64 learners
+            A.adacomp_unpack_update(table, gpu.packets, None, w, s1, None, gpu.ws, 1, 0.1, momentum=0.9)
+        assert e.value.code == -1
+        with pytest.raises(A.AdacompError):           # Adam without its second state
+            A.adacomp_unpack_update(table, gpu.packets[:2], None, w, s1, None, gpu.ws, 2, 0.1)
+        with pytest.raises(A.AdacompError):           # unknown optimizer
+            A.adacomp_unpack_update(table, gpu.packets[:2], None, w, s1, None, gpu.ws, 3, 0.1)
+        with pytest.raises(A.AdacompError):           # aliasing state
+            A.adacomp_unpack_update(table, gpu.packets[:2], None, w, w, None, gpu.ws, 1, 0.1)
+    finally:
+        gpu.close()
+
+
 def test_ties_and_zeros(H, oracle_lib):
     """Coarse dyadic grid: many equal magnitudes, exact cancellations to +-0, all-zero bins."""
     wl = W.custom("ties", [("a", 50 * 300 + 11, 50), ("b", 500 * 40 + 3, 500)])

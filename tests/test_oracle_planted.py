@@ -20,6 +20,14 @@ MUTANTS = {
     "H_from_residue_once": ("H[index] = G[index] + dW[index];", "H[index] = residue_in[index] + 2.0f * dW[index];"),
     "factor_not_reduced_by_one": ("float f_minus_1 = soft_factor - 1.0f;", "float f_minus_1 = soft_factor;"),
     "factor_applied_to_G": ("float extra = f_minus_1 * dW[index];", "float extra = f_minus_1 * G[index];"),
+    "sgd_no_average": ("float g = dense_sum[i] / n;      /* average among all learners */", "float g = dense_sum[i];"),
+    "sgd_plus_step": ("weights[i] = weights[i] - step;  /* w <- w - lr * v            */", "weights[i] = weights[i] + step;"),
+    "sgd_momentum_on_gradient": ("float mv = momentum * momentum_buf[i];", "float mv = momentum * g;"),
+    "sgd_step_uses_gradient": ("float step = lr * v;", "float step = lr * g;"),
+    "adam_v_not_squared": ("float g2 = g * g;", "float g2 = g;"),
+    "adam_no_bias_correction": ("float m_hat = m / bias1;                    /* bias1 = 1 - beta1^t                 */", "float m_hat = m;"),
+    "adam_eps_inside_sqrt": ("float denom = sqrtf(v_hat) + eps;", "float denom = sqrtf(v_hat + eps);"),
+    "adam_swapped_betas": ("float a = beta1 * m_buf[i], b = one_minus_b1 * g;", "float a = beta2 * m_buf[i], b = one_minus_b2 * g;"),
     "gmax_from_H": ("float a = fabsf(G[index]);", "float a = fabsf(H[index]);"),
     "gmax_signed": ("float a = fabsf(G[index]);", "float a = G[index];"),
     "bin_end_off_by_one": ("uint64_t lo = i * T, hi = lo + T < n ? lo + T : n;\n        float m = 0.0f;",
