@@ -481,22 +481,40 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     }
     woff += a.fixed_bytes;
 
+    // Eight words per lane and round, so that a tile with hundreds of words (short bins send several
+    // percent of their elements) costs a few memory round trips instead of one per 16 words.
     const uint32_t T = td.L_T, M = td.magic;
-    for (uint32_t p = sub; p < cnt; p += kPlaceLanes) {
-        const uint32_t s = p == sub ? s_first : uint32_t(stage[p]);
-        const uint32_t e = s >> 2, code = s & 3u;
-        const uint32_t b = bin_of(e, T, M);
-        const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
-        const uint64_t at = woff + uint64_t(base + p) * wbytes;
-        if (at + wbytes <= a.capacity) {
-            if (wbytes == 1u) packet[at] = uint8_t(word);
-            else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
+    constexpr uint32_t kU = 8;
+    for (uint32_t p0 = sub; p0 < cnt; p0 += kPlaceLanes * kU) {
+        uint32_t s[kU];
+        float g[kU];
+#pragma unroll
+        for (uint32_t u = 0; u < kU; ++u) {
+            const uint32_t p = p0 + kPlaceLanes * u;
+            s[u] = p < cnt ? (p == sub ? s_first : uint32_t(stage[p])) : 0u;  // 0: code 0, never a real entry
         }
-        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left there.
-        // (Staging G next to the word, to turn this read-modify-write into a plain store, was
-        // measured: it takes as much from k_fused as it saves here.)
-        const float g = rs[e];
-        rs[e] = code == 1u ? g - scale : g + scale;
+        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left in the
+        // residue: a read-modify-write, measured at a 64-byte read and a 32-byte write per word.
+        // (Keeping G next to the staged entry, so that this becomes a plain store, was built and
+        // measured twice, for all layers and for short-bin layers only: the scattered partial
+        // writes, not the reads, set the pace, and the extra store slows k_fused.)
+#pragma unroll
+        for (uint32_t u = 0; u < kU; ++u)
+            g[u] = (s[u] & 1u) ? rs[s[u] >> 2] : 0.f;
+#pragma unroll
+        for (uint32_t u = 0; u < kU; ++u) {
+            if (!(s[u] & 1u)) continue;  // codes are 1 or 3
+            const uint32_t p = p0 + kPlaceLanes * u;
+            const uint32_t e = s[u] >> 2, code = s[u] & 3u;
+            const uint32_t b = bin_of(e, T, M);
+            const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
+            const uint64_t at = woff + uint64_t(base + p) * wbytes;
+            if (at + wbytes <= a.capacity) {
+                if (wbytes == 1u) packet[at] = uint8_t(word);
+                else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
+            }
+            rs[e] = code == 1u ? g[u] - scale : g[u] + scale;
+        }
     }
 
     // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
