@@ -452,6 +452,57 @@ def test_deterministic_reruns(H):
     assert np.array_equal(outs[0][2].view(np.uint32), outs[1][2].view(np.uint32))
 
 
+def test_hip_graph_capture_and_replay(H, oracle_lib):
+    """compress_batch + unpack only launch kernels on the caller's stream (no allocation, copy or
+    synchronisation), so they can be captured in a HIP graph.  The graph is replayed several times
+    with eager work and synchronisations in between, and every replay is checked against the
+    free-running oracle."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(2)
+    table, n, nl = wl.table(), wl.n_total, 3
+    mask = G.layer_mask(table, n)
+    gpu = G.GpuSide(table, n, nl, batch=True)
+    other = G.GpuSide(table, n, 1)
+    try:
+        static_g = [torch.zeros(n, dtype=torch.float32, device=G.DEV) for _ in range(nl)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                       # warm-up outside capture
+            A.adacomp_compress_batch(table, static_g, gpu.residue, gpu.packets, gpu.ws)
+            A.adacomp_unpack_accumulate(table, gpu.packets, gpu.dense, gpu.ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            A.adacomp_compress_batch(table, static_g, gpu.residue, gpu.packets, gpu.ws)
+            A.adacomp_unpack_accumulate(table, gpu.packets, gpu.dense, gpu.ws)
+        for r in gpu.residue:
+            r.zero_()
+        R_cpu = [np.zeros(n, f32) for _ in range(nl)]
+        for t in range(5):
+            G.say(f"graph replay {t}")
+            grads = [W.gradient(wl, k, t) for k in range(nl)]
+            for k in range(nl):
+                static_g[k].copy_(torch.from_numpy(grads[k]))
+            for p in gpu.packets:
+                p.fill_(G.POISON)
+            graph.replay()
+            torch.cuda.synchronize()
+            want = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(nl)]
+            for k in range(nl):
+                G.compare_packet(gpu.packets[k].cpu().numpy(), want[k], gpu.capacity, f"replay {t} learner {k}")
+                G.compare_residue(gpu.residue[k].cpu().numpy(), R_cpu[k], mask, 1.0, f"replay {t} learner {k}")
+            dense = oracle_lib.unpack_accumulate(table, want, n)
+            assert np.array_equal(gpu.dense.cpu().numpy()[mask].view(np.uint32), dense[mask].view(np.uint32))
+            # eager work of the same library on other buffers between the replays
+            other.compress(0, grads[0])
+            other.unpack([0])
+    finally:
+        gpu.close()
+        other.close()
+
+
 def test_checkpoint_resume(H, oracle_lib):
     """The residue is the only learner state: copying it out and back resumes identically."""
     import gpu_harness as G
