@@ -696,8 +696,13 @@ __device__ __forceinline__ void apply_update(const UnpackArgs &a, float sum, flo
 template <int MODE>
 __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 {
-    const uint32_t tile = blockIdx.x;
+    // Workgroups go to the 8 XCDs round-robin by index, and every XCD has its own L2.  The tiles
+    // of one 64-bin chunk (8 consecutive tiles at L_T = 500) read the same count and offset lines
+    // of every packet, so inside each run of 64 workgroups the mapping is transposed: the 8
+    // workgroups that land on one XCD take 8 consecutive tiles.
+    uint32_t tile = blockIdx.x;
     if (tile >= a.n_tiles) return;
+    if (tile < (a.n_tiles & ~63u)) tile = (tile & ~63u) | ((tile & 7u) << 3) | ((tile >> 3) & 7u);
     const UTileDev ut = a.tiles[tile];
     const LayerDev ld = a.layers[ut.layer()];
     const uint32_t tid = threadIdx.x;
