@@ -91,8 +91,13 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
     // call streams one learner's buffers after the other instead of all of them at once
     const uint32_t lq = blockIdx.x / a.n_tiles;
-    const uint32_t tile = blockIdx.x - lq * a.n_tiles;
+    uint32_t tile = blockIdx.x - lq * a.n_tiles;
     const uint32_t lr = a.fused_first + lq;
+    // Workgroups go to the 8 XCDs round-robin by index.  Inside each run of 64 the mapping is
+    // transposed, so that the 8 workgroups landing on one XCD take 8 consecutive tiles (128 KB of
+    // each stream): measured 6-9 % faster than the identity on a plain triad with these tiles,
+    // and free of the slowdown of long launches.
+    if (tile < (a.n_tiles & ~63u)) tile = (tile & ~63u) | ((tile & 7u) << 3) | ((tile >> 3) & 7u);
     const TileDev td = a.tiles[tile];
     if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
