@@ -234,6 +234,14 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
  * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
 int adacomp_selftest_binindex(void);
 
+/* Tuning knob of adacomp_unpack_accumulate / adacomp_unpack_update, read by adacomp_workspace_init.
+ * A workgroup of the unpack kernel serves a run of up to 8 neighbouring output tiles (4096 elements
+ * each) that share their per-bin bookkeeping; the run length is halved until at least n_groups
+ * workgroups remain, so that small tables still fill the GPU.  Results do not depend on it.
+ * 0 restores the default (2048).  Process-wide; not synchronised with calls on other threads.
+ * Returns ADACOMP_OK. */
+int adacomp_tuning_unpack_min_groups(uint32_t n_groups);
+
 /* Per-kernel timing of the streaming kernel (k_fused) of adacomp_compress / adacomp_compress_batch
  * with HIP events on the caller's stream.  enable = k > 0 starts recording every k-th launch (and
  * clears earlier records; an event pair costs a few microseconds between back-to-back launches, so

@@ -22,7 +22,7 @@ EXPORTS = [
     "adacomp_compress", "adacomp_compress_batch", "adacomp_compress_variant",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
-    "adacomp_selftest_binindex", "adacomp_timing_enable", "adacomp_timing_read",
+    "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_timing_enable", "adacomp_timing_read",
 ]
 
 PACKET_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("status", "<u4"), ("n_layers", "<u4"),
@@ -84,6 +84,7 @@ def lib():
         L.adacomp_workspace_gmax.argtypes = [LP, u32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.adacomp_debug_keep_gmax.argtypes = [ctypes.c_int]
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
+        L.adacomp_tuning_unpack_min_groups.argtypes = [ctypes.c_uint32]
         L.adacomp_timing_enable.argtypes = [ctypes.c_int]
         L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64),
                                           ctypes.POINTER(ctypes.c_uint64)]
@@ -213,6 +214,11 @@ def adacomp_copy_f32(dst, src, n=None):
 
 def adacomp_selftest_binindex() -> int:
     return int(lib().adacomp_selftest_binindex())
+
+
+def adacomp_tuning_unpack_min_groups(n_groups: int):
+    """Workspaces initialised afterwards group unpack tiles only while n_groups workgroups remain; 0: default."""
+    _check(lib().adacomp_tuning_unpack_min_groups(int(n_groups)))
 
 
 def adacomp_timing_enable(every: int):

@@ -72,6 +72,8 @@ static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
     return ADACOMP_OK;
 }
 
+static uint32_t g_unpack_min_groups = kUnpackMinGroups;
+
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &p)
 {
     int rc = validate(layers, n_layers);
@@ -185,6 +187,44 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     }
     p.n_ctiles = uint32_t(n_ctiles);
     p.n_utiles = uint32_t(n_utiles);
+    if (tables) {
+        // ---- unpack groups: runs of tiles that share phase 1 (same layer and 64-bin chunk, or the
+        //      same long bin).  Longer runs save more table work but leave fewer workgroups, so the
+        //      run length halves until at least kUnpackMinGroups workgroups remain.  Workgroups
+        //      start in index order, so the runs get shorter towards the end of the table (the last
+        //      kUnpackTaperTiles tiles go alone, twice as many before them in pairs, ...): the
+        //      launch then ends with short workgroups instead of a few long stragglers. -----------
+        uint32_t run = kUnpackGroupTiles;
+        while (run > 1u && n_utiles / run < g_unpack_min_groups) run /= 2u;
+        const uint32_t taper = kUnpackTaperTiles;
+        const uint32_t run_max = run;
+        for (uint32_t i = 0; i < p.n_utiles; ++i) {
+            const UTileDev &ut = p.utiles[i];
+            const uint32_t left = p.n_utiles - i;
+            run = run_max;
+            for (uint32_t r = 1u, span = taper; r < run_max; r *= 2u, span += taper * r)
+                if (left <= span) { run = r; break; }
+            bool fresh = p.ugroups.empty() || p.ugroups.back().n_tiles >= run;
+            if (!fresh) {
+                const UTileDev &first = p.utiles[p.ugroups.back().first_tile];
+                fresh = first.layer() != ut.layer() ||
+                        (ut.L_T <= kUnpackTileElems ? (first.first_bin >> 6) != (ut.first_bin >> 6) : first.first_bin != ut.first_bin);
+            }
+            if (fresh) p.ugroups.push_back(UGroupDev{i, 1u});
+            else ++p.ugroups.back().n_tiles;
+        }
+        // Single tiles, for the launches that also apply the optimizer: those are bound by the
+        // traffic of their epilogue, gain nothing from shared tables, and with runs of tiles they
+        // were up to 15 % slower on some machines.  Workgroups are dealt to the 8 XCDs round-robin,
+        // so inside each 64 the order is transposed and the 8 tiles of a chunk, which read the same
+        // count and offset lines of every packet, share an L2.
+        p.usingles.resize(p.n_utiles);
+        const uint32_t whole = p.n_utiles & ~63u;
+        for (uint32_t i = 0; i < p.n_utiles; ++i)
+            p.usingles[i] = UGroupDev{i < whole ? ((i & ~63u) | ((i & 7u) << 3) | ((i >> 3) & 7u)) : i, 1u};
+        if (run_max == 1u) p.ugroups = p.usingles;
+        p.n_ugroups = uint32_t(p.ugroups.size());
+    }
     p.n_bins_total = uint32_t(bins_total);
     p.n_chunks_total = uint32_t(chunks_total);
     p.fixed_bytes = fixed;
@@ -196,6 +236,8 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     w.layers = off;      off = pad256(off + sizeof(LayerDev) * size_t(n_layers));
     w.ctiles = off;      off = pad256(off + sizeof(TileDev) * size_t(p.n_ctiles));
     w.utiles = off;      off = pad256(off + sizeof(UTileDev) * size_t(p.n_utiles));
+    w.ugroups = off;     off = pad256(off + sizeof(UGroupDev) * size_t(p.n_utiles));  // at most one group per tile
+    w.usingles = off;    off = pad256(off + sizeof(UGroupDev) * size_t(p.n_utiles));
     w.scratch = off;
     off = 0;             // offsets inside one learner's scratch block
     w.tile_out = off;    off = pad256(off + sizeof(TileOut) * size_t(p.n_ctiles));
@@ -225,7 +267,7 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     if (p.n_layers != n_layers || p.table_hash != hash_table(layers, n_layers)) return ADACOMP_EWORKSPACE;
     if (workspace_bytes < p.ws.total(n_learners) || it->second.bytes < p.ws.total(n_learners)) return ADACOMP_EWORKSPACE;
     // copy the scalars only; the tables already live on the device
-    out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles;
+    out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles; out.n_ugroups = p.n_ugroups;
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
@@ -305,11 +347,15 @@ int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, voi
     char *ws = static_cast<char *>(workspace);
     if (hipMemcpy(ws + p.ws.layers, p.layers.data(), sizeof(LayerDev) * p.layers.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ws + p.ws.ctiles, p.ctiles.data(), sizeof(TileDev) * p.ctiles.size(), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(ws + p.ws.utiles, p.utiles.data(), sizeof(UTileDev) * p.utiles.size(), hipMemcpyHostToDevice) != hipSuccess)
+        hipMemcpy(ws + p.ws.utiles, p.utiles.data(), sizeof(UTileDev) * p.utiles.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(ws + p.ws.ugroups, p.ugroups.data(), sizeof(UGroupDev) * p.ugroups.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(ws + p.ws.usingles, p.usingles.data(), sizeof(UGroupDev) * p.usingles.size(), hipMemcpyHostToDevice) != hipSuccess)
         return ADACOMP_EHIP;
     // the host copies of the tile tables are no longer needed
     p.ctiles.clear(); p.ctiles.shrink_to_fit();
     p.utiles.clear(); p.utiles.shrink_to_fit();
+    p.ugroups.clear(); p.ugroups.shrink_to_fit();
+    p.usingles.clear(); p.usingles.shrink_to_fit();
     std::lock_guard<std::mutex> lk(g_mu);
     reg.bytes = workspace_bytes;
     g_ws[workspace] = std::move(reg);
@@ -456,6 +502,9 @@ static int unpack_common(const adacomp_layer_t *layers, uint32_t n_layers, const
         a.accumulate = done > 0;
         a.mode = (opt && last) ? opt->kind : 0u;
         a.write_dense = dense_out != nullptr;
+        // runs of tiles per workgroup for the plain sum, single tiles when the optimizer step follows
+        a.groups = reinterpret_cast<const UGroupDev *>(ws + (a.mode == 0u ? p.ws.ugroups : p.ws.usingles));
+        a.n_groups = a.mode == 0u ? p.n_ugroups : p.n_utiles;
         for (uint32_t k = 0; k < kMaxPacketArgs; ++k)
             a.packets[k] = k < now ? static_cast<const uint8_t *>(packets[done + k]) : nullptr;
         if ((rc = launch_unpack(a, hip_stream)) != ADACOMP_OK) return rc;
@@ -528,6 +577,12 @@ int adacomp_selftest_binindex(void)
 int adacomp_debug_keep_gmax(int enable)
 {
     g_keep_gmax = enable != 0;
+    return ADACOMP_OK;
+}
+
+int adacomp_tuning_unpack_min_groups(uint32_t n_groups)
+{
+    g_unpack_min_groups = n_groups ? n_groups : kUnpackMinGroups;
     return ADACOMP_OK;
 }
 

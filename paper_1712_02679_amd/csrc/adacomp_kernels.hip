@@ -18,7 +18,8 @@
 //            about 1-10 % of the elements); one extra workgroup writes header and records.
 // adacomp_unpack_accumulate is one launch, k_unpack: a workgroup owns a tile of the dense output
 // in LDS, a lane group owns each bin and adds the learners' +-scale in learner order, then the
-// tile is written out once with coalesced float4 stores.
+// tile is written out once with coalesced float4 stores; neighbouring tiles share a workgroup
+// and the per-bin bookkeeping.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -532,135 +533,150 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 
 // ==============================================================================================
 // k_unpack: dense_out <- sum over learners, in learner order, of the decoded packets.
-// A workgroup owns a tile of the output in LDS.  Per group of 16 learners it first gathers, for
-// every (bin, learner) of the tile, the word count and the position of the first word (one wave
-// per learner, all learners' loads in flight together), then a lane group per bin reads the 16
-// learners' table entries with a few wide LDS loads, fetches the words of all 16 learners, and
-// adds +-scale with LDS float atomics in learner order.  All adds to one address come from one
-// wave in program order and the LDS unit executes a wave's operations in order, so the sum
-// order is fixed: learner 0 first.  (LDS float adds round to nearest even and keep denormals,
-// like v_add_f32.)
+// A workgroup owns a tile of the output in LDS, and serves a run of up to 8 neighbouring tiles one
+// after the other.  Phase 1 gathers, for every (bin, learner) of the run, the word count and the
+// position of the first word (one wave per learner, all learners' loads in flight together); with
+// up to 16 learners this is done once per run, which is what the runs are for: at L_T = 500 the
+// 8 tiles of a 64-bin chunk need the same count lines and the same prefix sums.  Phase 2, per
+// tile: a lane group per bin reads the 16 learners' table entries with a few wide LDS loads,
+// fetches the words of all 16 learners, and adds +-scale with LDS float atomics in learner order.
+// All adds to one address come from one wave in program order and the LDS unit executes a wave's
+// operations in order, so the sum order is fixed: learner 0 first.  (LDS float adds round to
+// nearest even and keep denormals, like v_add_f32.)  On the 125 M-element table with 16 learners
+// a pass that only clears and writes the tiles takes 88 us, phase 1 per tile added 79 us and
+// phase 2 adds 63 us; sharing phase 1 over a run brought the whole launch from 230-250 to 185 us.
 // ==============================================================================================
+// Phase 1 for learners k0 .. k0 + 15 and the bins [row0_bin, scan_end) of one 64-bin chunk: word
+// count and position of the first word of every (bin, learner), into the LDS tables (row = bin -
+// row0_bin).  The caller has a barrier before (the tables are free) and after (they are filled).
 template <bool W8>
-__device__ __forceinline__ void unpack_tile(const UnpackArgs &a, const UTileDev &ut, const LayerDev &ld,
-                                            float *s_acc, uint32_t (*s_off)[kLearnerGroup],
-                                            uint16_t (*s_cnt)[kLearnerGroup], float *s_scale, uint32_t *s_cmax)
+__device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDev &ld, const uint32_t layer,
+                                              const uint32_t row0_bin, const uint32_t scan_end, const uint32_t k0,
+                                              uint32_t (*s_off)[kLearnerGroup], uint16_t (*s_cnt)[kLearnerGroup],
+                                              float *s_scale, uint32_t *s_cmax)
 {
     typedef typename std::conditional<W8, uint8_t, uint16_t>::type word_t;
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
-    const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
-    const uint32_t chunk = ut.first_bin >> 6;
-    const uint32_t b = (chunk << 6) + lane;           // the bin this lane looks up in phase 1
-    const bool in_scan = b < ut.first_bin + nb;       // bins of the chunk up to the end of the tile
-    const bool in_tile = in_scan && b >= ut.first_bin;
+    const uint32_t chunk = row0_bin >> 6;
+    const uint32_t b = (chunk << 6) + lane;           // the bin this lane looks up
+    const bool in_scan = b < scan_end;                // bins of the chunk up to the end of the group
+    const bool in_rows = in_scan && b >= row0_bin;
     constexpr uint32_t kPerWave = kLearnerGroup / 4u;
+    const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
 
-    for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
-        const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
-        __syncthreads();  // accumulators initialised / previous group finished with the tables
-        if (tid == 0) *s_cmax = 0u;
-        __syncthreads();
+    if (tid == 0) *s_cmax = 0u;
+    __syncthreads();
 
-        // ---- phase 1: wave w serves learners w, w + 4, ...; all their loads are issued first ----
-        uint32_t c[kPerWave], coff[kPerWave], wbase[kPerWave];
-        float sc[kPerWave];
-        bool ok[kPerWave];
+    // wave w serves learners w, w + 4, ...; all their loads are issued first
+    uint32_t c[kPerWave], coff[kPerWave], wbase[kPerWave];
+    float sc[kPerWave];
+    bool ok[kPerWave];
 #pragma unroll
-        for (uint32_t q = 0; q < kPerWave; ++q) {
-            const uint32_t kk = wave + 4u * q;
-            c[q] = 0u; coff[q] = 0u; wbase[q] = 0u; sc[q] = 0.f; ok[q] = false;
-            if (kk < nk) {
-                const uint8_t *pk = a.packets[k0 + kk];
-                const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers
-                ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
-                        (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
-                // counts and chunk offsets sit in the fixed part, which every packet buffer holds
-                if (in_scan) c[q] = reinterpret_cast<const word_t *>(pk + ld.counts_offset)[b];
-                coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
-                const adacomp_packet_layer_t *rec =
-                    reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + ut.layer();
-                sc[q] = rec->scale;
-                wbase[q] = uint32_t(rec->words_offset / sizeof(word_t));  // packets stay below 2^32 words (host check)
-            }
+    for (uint32_t q = 0; q < kPerWave; ++q) {
+        const uint32_t kk = wave + 4u * q;
+        c[q] = 0u; coff[q] = 0u; wbase[q] = 0u; sc[q] = 0.f; ok[q] = false;
+        if (kk < nk) {
+            const uint8_t *pk = a.packets[k0 + kk];
+            const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers
+            ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
+                    (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
+            // counts and chunk offsets sit in the fixed part, which every packet buffer holds
+            if (in_scan) c[q] = reinterpret_cast<const word_t *>(pk + ld.counts_offset)[b];
+            coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
+            const adacomp_packet_layer_t *rec =
+                reinterpret_cast<const adacomp_packet_layer_t *>(pk + sizeof(adacomp_packet_header_t)) + layer;
+            sc[q] = rec->scale;
+            wbase[q] = uint32_t(rec->words_offset / sizeof(word_t));  // packets stay below 2^32 words (host check)
         }
-        uint32_t wmax = 0u;
+    }
+    uint32_t wmax = 0u;
 #pragma unroll
-        for (uint32_t q = 0; q < kPerWave; ++q) {
-            const uint32_t kk = wave + 4u * q;  // < kLearnerGroup; learners past nk get empty entries
-            const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
-            const uint32_t incl = wave_incl_scan(cq, lane);
-            if (in_tile) {
-                s_off[b - ut.first_bin][kk] = wbase[q] + coff[q] + incl - cq;
-                s_cnt[b - ut.first_bin][kk] = uint16_t(cq);
-            }
-            if (lane == 0) s_scale[kk] = sc[q];
-            wmax = (in_tile && cq > wmax) ? cq : wmax;
+    for (uint32_t q = 0; q < kPerWave; ++q) {
+        const uint32_t kk = wave + 4u * q;  // < kLearnerGroup; learners past nk get empty entries
+        const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
+        const uint32_t incl = wave_incl_scan(cq, lane);
+        if (in_rows) {
+            s_off[b - row0_bin][kk] = wbase[q] + coff[q] + incl - cq;
+            s_cnt[b - row0_bin][kk] = uint16_t(cq);
         }
+        if (lane == 0) s_scale[kk] = sc[q];
+        wmax = (in_rows && cq > wmax) ? cq : wmax;
+    }
 #pragma unroll
-        for (uint32_t d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(wmax, d, 64); wmax = o > wmax ? o : wmax; }
-        if (lane == 0) atomicMax(s_cmax, wmax);
-        __syncthreads();
-        // lanes per bin: the smallest power of two that holds the tile's largest word count, between
-        // the table's default (8 or 16) and the whole wave
-        uint32_t glog = ut.group_log2();
-        while (glog < 6u && (1u << glog) < *s_cmax) ++glog;
-        const uint32_t gsz = 1u << glog;
+    for (uint32_t d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(wmax, d, 64); wmax = o > wmax ? o : wmax; }
+    if (lane == 0) atomicMax(s_cmax, wmax);
+}
 
-        // ---- phase 2: a lane group owns a bin --------------------------------------------------
-        float scl[kLearnerGroup];
+// Phase 2 for one tile: a lane group owns a bin (table row row0 + bin index inside the tile).
+template <bool W8>
+__device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev &ut, const uint32_t row0, const uint32_t k0,
+                                            float *s_acc, uint32_t (*s_off)[kLearnerGroup],
+                                            uint16_t (*s_cnt)[kLearnerGroup], const float *s_scale, const uint32_t *s_cmax)
+{
+    typedef typename std::conditional<W8, uint8_t, uint16_t>::type word_t;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
+    const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
+    // lanes per bin: the smallest power of two that holds the largest word count of the tables,
+    // between the layer's default (8 or 16) and the whole wave
+    uint32_t glog = ut.group_log2();
+    while (glog < 6u && (1u << glog) < *s_cmax) ++glog;
+    const uint32_t gsz = 1u << glog;
+
+    float scl[kLearnerGroup];
+#pragma unroll
+    for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
+        const float4 t = *reinterpret_cast<const float4 *>(&s_scale[4u * v]);
+        scl[4 * v] = t.x; scl[4 * v + 1] = t.y; scl[4 * v + 2] = t.z; scl[4 * v + 3] = t.w;
+    }
+    for (uint32_t s = tid; s < (nb << glog); s += kWG) {
+        const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
+        const uint32_t row = row0 + lb;
+        const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
+        float *acc = s_acc + lb * T;
+        uint32_t cc[kLearnerGroup], off[kLearnerGroup];
+#pragma unroll
+        for (uint32_t v = 0; v < kLearnerGroup / 8u; ++v) {
+            const uint4 t = *reinterpret_cast<const uint4 *>(&s_cnt[row][8u * v]);
+            cc[8 * v] = t.x & 0xFFFFu; cc[8 * v + 1] = t.x >> 16; cc[8 * v + 2] = t.y & 0xFFFFu; cc[8 * v + 3] = t.y >> 16;
+            cc[8 * v + 4] = t.z & 0xFFFFu; cc[8 * v + 5] = t.z >> 16; cc[8 * v + 6] = t.w & 0xFFFFu; cc[8 * v + 7] = t.w >> 16;
+        }
 #pragma unroll
         for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
-            const float4 t = *reinterpret_cast<const float4 *>(&s_scale[4u * v]);
-            scl[4 * v] = t.x; scl[4 * v + 1] = t.y; scl[4 * v + 2] = t.z; scl[4 * v + 3] = t.w;
+            const uint4 t = *reinterpret_cast<const uint4 *>(&s_off[row][4u * v]);
+            off[4 * v] = t.x; off[4 * v + 1] = t.y; off[4 * v + 2] = t.z; off[4 * v + 3] = t.w;
         }
-        for (uint32_t s = tid; s < (nb << glog); s += kWG) {
-            const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
-            const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
-            float *acc = s_acc + lb * T;
-            uint32_t cc[kLearnerGroup], off[kLearnerGroup];
+        uint32_t word[kLearnerGroup];
+        uint32_t cmax = 0u;
 #pragma unroll
-            for (uint32_t v = 0; v < kLearnerGroup / 8u; ++v) {
-                const uint4 t = *reinterpret_cast<const uint4 *>(&s_cnt[lb][8u * v]);
-                cc[8 * v] = t.x & 0xFFFFu; cc[8 * v + 1] = t.x >> 16; cc[8 * v + 2] = t.y & 0xFFFFu; cc[8 * v + 3] = t.y >> 16;
-                cc[8 * v + 4] = t.z & 0xFFFFu; cc[8 * v + 5] = t.z >> 16; cc[8 * v + 6] = t.w & 0xFFFFu; cc[8 * v + 7] = t.w >> 16;
+        for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
+            cmax = cc[kk] > cmax ? cc[kk] : cmax;
+            word[kk] = 0u;
+            if (sub < cc[kk]) {
+                const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + (kk < nk ? kk : 0u)]);
+                word[kk] = wp[off[kk] + sub];
             }
-#pragma unroll
-            for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
-                const uint4 t = *reinterpret_cast<const uint4 *>(&s_off[lb][4u * v]);
-                off[4 * v] = t.x; off[4 * v + 1] = t.y; off[4 * v + 2] = t.z; off[4 * v + 3] = t.w;
-            }
-            uint32_t word[kLearnerGroup];
-            uint32_t cmax = 0u;
+        }
+        if (cmax <= gsz) {
 #pragma unroll
             for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
-                cmax = cc[kk] > cmax ? cc[kk] : cmax;
-                word[kk] = 0u;
-                if (sub < cc[kk]) {
-                    const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + (kk < nk ? kk : 0u)]);
-                    word[kk] = wp[off[kk] + sub];
-                }
+                const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
+                const uint32_t code = word[kk] & 3u;
+                if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? scl[kk] : -scl[kk]);
             }
-            if (cmax <= gsz) {
-#pragma unroll
-                for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
-                    const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
-                    const uint32_t code = word[kk] & 3u;
-                    if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? scl[kk] : -scl[kk]);
-                }
-            } else {
-                // some learner sends more words from this bin than the group has lanes: plain loops,
-                // one learner after the other (same order)
-                for (uint32_t kk = 0; kk < nk; ++kk) {
-                    const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + kk]);
-                    const uint32_t cck = s_cnt[lb][kk], st = s_off[lb][kk];
-                    const float sck = s_scale[kk];
-                    for (uint32_t jw = sub; jw < cck; jw += gsz) {
-                        const uint32_t wd = wp[st + jw];
-                        const uint32_t idx = (wd >> 2) - ut.idx_lo;
-                        const uint32_t code = wd & 3u;
-                        if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
-                    }
+        } else {
+            // some learner sends more words from this bin than the group has lanes: plain loops,
+            // one learner after the other (same order)
+            for (uint32_t kk = 0; kk < nk; ++kk) {
+                const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + kk]);
+                const uint32_t cck = s_cnt[row][kk], st = s_off[row][kk];
+                const float sck = s_scale[kk];
+                for (uint32_t jw = sub; jw < cck; jw += gsz) {
+                    const uint32_t wd = wp[st + jw];
+                    const uint32_t idx = (wd >> 2) - ut.idx_lo;
+                    const uint32_t code = wd & 3u;
+                    if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
                 }
             }
         }
@@ -701,26 +717,32 @@ __device__ __forceinline__ void apply_update(const UnpackArgs &a, float sum, flo
 template <int MODE>
 __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
 {
-    // Workgroups go to the 8 XCDs round-robin by index, and every XCD has its own L2.  The tiles
-    // of one 64-bin chunk (8 consecutive tiles at L_T = 500) read the same count and offset lines
-    // of every packet, so inside each run of 64 workgroups the mapping is transposed: the 8
-    // workgroups that land on one XCD take 8 consecutive tiles.
-    uint32_t tile = blockIdx.x;
-    if (tile >= a.n_tiles) return;
-    if (tile < (a.n_tiles & ~63u)) tile = (tile & ~63u) | ((tile & 7u) << 3) | ((tile >> 3) & 7u);
-    const UTileDev ut = a.tiles[tile];
-    const LayerDev ld = a.layers[ut.layer()];
+    // A workgroup serves a group of consecutive tiles that lie in one 64-bin chunk (or are slices
+    // of one long bin).  With up to 16 learners the tables of phase 1 are built once for the group.
+    if (blockIdx.x >= a.n_groups) return;
+    const UGroupDev grp = a.groups[blockIdx.x];
+    const UTileDev ut0 = a.tiles[grp.first_tile];
+    const UTileDev ut_last = a.tiles[grp.first_tile + grp.n_tiles - 1u];
+    const uint32_t layer = ut0.layer();
+    const LayerDev ld = a.layers[layer];
     const uint32_t tid = threadIdx.x;
-    const uint32_t n = ut.n_elems;
-    const bool vec = ut.aligned();
-    float *__restrict__ out = a.dense + ut.elem_base;
+    const uint32_t row0_bin = ut0.first_bin, scan_end = ut_last.first_bin + ut_last.n_bins;
+    const bool tables_once = a.n_learners <= kLearnerGroup;
+    const bool w8 = ld.word_bytes == 1u;
 
     __shared__ float s_acc[kUnpackTileElems];
     __shared__ __attribute__((aligned(16))) uint32_t s_off[64][kLearnerGroup];  // first word of (bin, learner), counted from the packet start
     __shared__ __attribute__((aligned(16))) uint16_t s_cnt[64][kLearnerGroup];
     __shared__ __attribute__((aligned(16))) float s_scale[kLearnerGroup];
-    __shared__ uint32_t s_cmax;                                                // largest word count of a (bin, learner) in the tile
+    __shared__ uint32_t s_cmax;                                                // largest word count of a (bin, learner) in the tables
 
+  for (uint32_t ti = 0; ti < grp.n_tiles; ++ti) {
+    const UTileDev ut = ti == 0u ? ut0 : a.tiles[grp.first_tile + ti];
+    const uint32_t n = ut.n_elems;
+    const bool vec = ut.aligned();
+    float *__restrict__ out = a.dense + ut.elem_base;
+
+    __syncthreads();  // the previous tile has been written out and its adds are done with the tables
     // ---- tile accumulators: zero, or the partial sum of an earlier launch ----------------------
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -736,8 +758,16 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
         *reinterpret_cast<float4 *>(&s_acc[i]) = v;  // s_acc has room for the rounded-up tail
     }
 
-    if (ld.word_bytes == 1u) unpack_tile<true>(a, ut, ld, s_acc, s_off, s_cnt, s_scale, &s_cmax);
-    else unpack_tile<false>(a, ut, ld, s_acc, s_off, s_cnt, s_scale, &s_cmax);
+    for (uint32_t k0 = 0; k0 < a.n_learners; k0 += kLearnerGroup) {
+        if (!tables_once || ti == 0u) {
+            if (k0 != 0u) __syncthreads();  // the adds of the previous 16 learners are done with the tables
+            if (w8) unpack_tables<true>(a, ld, layer, row0_bin, scan_end, k0, s_off, s_cnt, s_scale, &s_cmax);
+            else unpack_tables<false>(a, ld, layer, row0_bin, scan_end, k0, s_off, s_cnt, s_scale, &s_cmax);
+        }
+        __syncthreads();  // tables filled, accumulators initialised
+        if (w8) unpack_adds<true>(a, ut, ut.first_bin - row0_bin, k0, s_acc, s_off, s_cnt, s_scale, &s_cmax);
+        else unpack_adds<false>(a, ut, ut.first_bin - row0_bin, k0, s_acc, s_off, s_cnt, s_scale, &s_cmax);
+    }
     __syncthreads();
 
     for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
@@ -776,6 +806,7 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
             }
         }
     }
+  }  // tiles of the group
 }
 
 // ==============================================================================================
@@ -825,9 +856,9 @@ int launch_place(const CompressArgs &a, void *stream)
 int launch_unpack(const UnpackArgs &a, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (a.mode == 1) hipLaunchKernelGGL(k_unpack<1>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
-    else if (a.mode == 2) hipLaunchKernelGGL(k_unpack<2>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
-    else hipLaunchKernelGGL(k_unpack<0>, dim3(a.n_tiles), dim3(kWG), 0, s, a);
+    if (a.mode == 1) hipLaunchKernelGGL(k_unpack<1>, dim3(a.n_groups), dim3(kWG), 0, s, a);
+    else if (a.mode == 2) hipLaunchKernelGGL(k_unpack<2>, dim3(a.n_groups), dim3(kWG), 0, s, a);
+    else hipLaunchKernelGGL(k_unpack<0>, dim3(a.n_groups), dim3(kWG), 0, s, a);
     return check_launch();
 }
 

@@ -59,6 +59,15 @@ struct UTileDev {
 };
 static_assert(sizeof(UTileDev) == 32, "UTileDev layout");
 
+// Consecutive unpack tiles served by one workgroup: tiles of one 64-bin chunk, or slices of one bin.
+struct UGroupDev {
+    uint32_t first_tile, n_tiles;
+};
+static_assert(sizeof(UGroupDev) == 8, "UGroupDev layout");
+constexpr uint32_t kUnpackGroupTiles = 8;   // at most this many tiles per group
+constexpr uint32_t kUnpackMinGroups = 2048;  // groups of more than one tile only while this many workgroups remain (8 per compute unit)
+constexpr uint32_t kUnpackTaperTiles = 768;  // tiles at the end of the table that go alone (3 per compute unit)
+
 // What k_fused leaves per tile for k_scan and k_place: one 16-byte record, so that a tile makes one
 // small store here instead of three.
 struct TileOut {
@@ -71,7 +80,7 @@ static_assert(sizeof(TileOut) == 16, "TileOut layout");
 // Byte offsets inside the caller's workspace.  The tables come first; then one scratch block per
 // learner of a batched call (a single-learner call uses block 0).
 struct WorkspaceLayout {
-    size_t layers = 0, ctiles = 0, utiles = 0;          // tables written by workspace_init
+    size_t layers = 0, ctiles = 0, utiles = 0, ugroups = 0, usingles = 0;  // tables written by workspace_init
     size_t scratch = 0;                                 // first scratch block
     size_t scratch_stride = 0;                          // bytes per learner
     // offsets inside a scratch block
@@ -84,7 +93,7 @@ struct WorkspaceLayout {
 
 struct Plan {
     uint32_t n_layers = 0;
-    uint32_t n_ctiles = 0, n_utiles = 0;
+    uint32_t n_ctiles = 0, n_utiles = 0, n_ugroups = 0;
     uint32_t n_bins_total = 0, n_chunks_total = 0;
     uint64_t elem_span = 0;     // max over layers of elem_offset + n_elems
     uint64_t n_elems_total = 0;
@@ -96,6 +105,7 @@ struct Plan {
     std::vector<LayerDev> layers;
     std::vector<TileDev> ctiles;
     std::vector<UTileDev> utiles;
+    std::vector<UGroupDev> ugroups, usingles;
 };
 
 // Validates the table (ADACOMP_E* on failure) and, with tables = true, fills the tile tables.
@@ -128,8 +138,10 @@ struct CompressArgs {
 
 struct UnpackArgs {
     const UTileDev *tiles;
+    const UGroupDev *groups;
     const LayerDev *layers;
     float *dense;
+    uint32_t n_groups;
     uint32_t n_tiles, n_layers, n_learners, accumulate;
     uint32_t write_dense;              // 0: the sum is only consumed by the update
     uint32_t mode;                     // 0: sum only; 1: SGD with momentum; 2: Adam (applied by this launch)

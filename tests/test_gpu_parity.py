@@ -345,6 +345,44 @@ def test_unpack_update_many_learners_and_errors(H, oracle_lib):
         gpu.close()
 
 
+# ------------------------------------------------------------------------------------------------
+# unpack with runs of tiles per workgroup (large tables do this by default; here the threshold is
+# lowered so that every small table does, including the shortened runs at the end of the table)
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture
+def grouped_unpack_tiles():
+    import paper_1712_02679_amd as A
+    A.adacomp_tuning_unpack_min_groups(1)
+    yield
+    A.adacomp_tuning_unpack_min_groups(0)
+
+
+GROUPED_TABLES = dict(EDGE_TABLES)
+GROUPED_TABLES["LT500_many_tiles"] = [("a", 500 * 64 * 40 + 333, 500), ("b", 3000 * 64 * 3 + 5, 3000)]
+GROUPED_TABLES["LT16384_many_slices"] = [("a", 16384 * 30 + 4100, 16384), ("b", 4097 * 70, 4097)]
+
+
+@pytest.mark.parametrize("name", sorted(GROUPED_TABLES))
+def test_grouped_unpack_tables(H, oracle_lib, grouped_unpack_tiles, name):
+    wl = W.custom(name, GROUPED_TABLES[name], dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 2, seed=17, label="grouped unpack " + name, batch=True, check_gmax=False)
+
+
+def test_grouped_unpack_many_learners(H, oracle_lib, grouped_unpack_tiles):
+    """More than 16 learners (the tables are rebuilt per tile) and more than 64 (a second launch
+    that accumulates)."""
+    wl = W.custom("grp70", [("a", 50 * 200 + 7, 50), ("b", 500 * 150 + 11, 500), ("c", 9000 * 3 + 1, 9000)])
+    H.run_parity(oracle_lib, wl, 20, 2, seed=4, batch=True, check_gmax=False)
+    H.run_parity(oracle_lib, wl, 70, 1, seed=5, batch=True, check_gmax=False)
+
+
+@pytest.mark.parametrize("kind", [1, 2])
+def test_grouped_unpack_update(H, oracle_lib, grouped_unpack_tiles, kind):
+    wl = W.custom("grp_upd", GROUPED_TABLES["LT500_many_tiles"] + [("z", 16383 * 2 + 7, 16383), ("y", 777, 9)], dist="normal_outliers")
+    _update_case(oracle_lib, wl, 3, 2, kind, True, seed=6)
+    _update_case(oracle_lib, wl, 18, 1, kind, False, seed=7)
+
+
 def test_ties_and_zeros(H, oracle_lib):
     """Coarse dyadic grid: many equal magnitudes, exact cancellations to +-0, all-zero bins."""
     wl = W.custom("ties", [("a", 50 * 300 + 11, 50), ("b", 500 * 40 + 3, 500)])
