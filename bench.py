@@ -250,6 +250,19 @@ def main():
         cpu = {"value": round(n_cpu * 4 * n_params / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} learner(s) x 1 step of {wl.name} (compress each, then one unpack of "
                          f"{n_cpu} packets), single thread, {dt:.1f}s of oracle time"}
+        # the same oracle with one learner per host thread (learners are independent; the oracle itself
+        # stays single-threaded), then the one unpack: what the host's cores give on the same step
+        from concurrent.futures import ThreadPoolExecutor
+        n_thr = min(n_learners, len(os.sched_getaffinity(0)), 16)
+        hosts = [(grads[k].cpu().numpy(), np.zeros(n_total, np.float32)) for k in range(n_learners)]
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(n_thr) as pool:
+            pk = list(pool.map(lambda gr: orc.compress(table, gr[0], gr[1]), hosts))
+        orc.unpack_accumulate(table, pk, n_total)
+        dt_all = time.perf_counter() - t1
+        cpu["all_cores"] = {"value": round(n_learners * 4 * n_params / dt_all / 1e9, 4), "unit": "GB/s", "cores": n_thr,
+                            "sample": f"{n_learners} learner(s) x 1 step, one learner per thread, then one unpack, {dt_all:.1f}s"}
+        del hosts, pk
 
     out = {
         "metric": "GB/s gradient compressed+unpacked", "value": round(value, 2), "unit": "GB/s",

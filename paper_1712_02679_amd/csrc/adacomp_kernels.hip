@@ -103,14 +103,10 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
-    uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
-    float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
     float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
     uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
     uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
     uint8_t *const packet = a.packet[lr];
-    (void)tile_out; (void)layer_nsel; (void)layer_scale;
-    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
 
     __shared__ uint32_t s_gmax[kMaxTileBins];  // bit pattern of max |G|: for non-negative floats the
     __shared__ uint32_t s_cnt[kMaxTileBins];   // unsigned integer order is the float order
@@ -315,12 +311,6 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
     uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
     float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
-    float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
-    uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
-    uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
-    uint8_t *const packet = a.packet[lr];
-    (void)tile_out; (void)layer_nsel; (void)layer_scale;
-    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
     const LayerDev ld = a.layers[l];
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
@@ -394,12 +384,9 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
     uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
     float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
-    float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
     uint32_t *const chunk_rel = reinterpret_cast<uint32_t *>(sb + a.o_chunk_rel);
     uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
     uint8_t *const packet = a.packet[lr];
-    (void)tile_out; (void)layer_nsel; (void)layer_scale;
-    (void)gmax_out; (void)chunk_rel; (void)stage_all; (void)packet;
 
     if (blockIdx.x == gridDim.x - 1) {
         // ---- header, layer records, zero padding: 256 layers at a time, word offsets by a block

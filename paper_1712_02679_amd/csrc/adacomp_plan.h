@@ -12,7 +12,9 @@ namespace adacomp {
 
 constexpr uint32_t kWG = 256;            // threads per workgroup in every kernel (4 wave64)
 constexpr uint32_t kMaxTileBins = 1024;  // bins per compress tile (LDS arrays)
-constexpr uint32_t kUnpackTileElems = 4096;  // elements per unpack tile (16 KB of LDS accumulators; 8192 is 10 % faster for the plain sum but 12 % slower with the optimizer epilogue)
+// elements per unpack tile: 16 KB of LDS accumulators (8192 was 10 % faster for the plain sum but
+// 12 % slower with the optimizer epilogue)
+constexpr uint32_t kUnpackTileElems = 4096;
 constexpr uint32_t kLearnerGroup = 16;   // learners whose bin tables sit in LDS together in unpack
 constexpr uint32_t kMaxPacketArgs = 64;  // packet pointers passed by value per unpack launch
 
