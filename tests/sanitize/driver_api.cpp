@@ -6,7 +6,99 @@
 #include <cstdlib>
 #include <vector>
 
+#include <hip/hip_runtime.h>
+
 #include "adacomp.h"
+#include "adacomp_plan.h"
+
+// Invariants of the tile tables that the kernels index without further checks: every table is
+// built on the host, so everything the kernels assume about it can be verified here.
+static uint64_t g_tiles_checked = 0, g_groups_checked = 0;
+
+static int check_plan(const std::vector<adacomp_layer_t> &t)
+{
+    using namespace adacomp;
+    Plan p;
+    if (build_plan(t.data(), uint32_t(t.size()), true, p) != ADACOMP_OK) return 100;
+    if (p.ctiles.size() != p.n_ctiles || p.utiles.size() != p.n_utiles || p.ugroups.size() != p.n_ugroups ||
+        p.usingles.size() != p.n_utiles)
+        return 101;
+    // compress tiles: whole bins, in order, covering each layer exactly; sizes fit the register class
+    uint32_t ct = 0;
+    for (uint32_t l = 0; l < p.n_layers; ++l) {
+        const LayerDev &ld = p.layers[l];
+        if (ld.ctile_start != ct) return 102;
+        uint64_t e = 0;
+        uint32_t bin = 0;
+        for (uint32_t i = 0; i < ld.n_ctiles; ++i, ++ct) {
+            const TileDev &td = p.ctiles[ct];
+            const uint32_t cap = 4096u << td.jcode();
+            if (td.layer() != l || td.L_T != ld.L_T || td.first_bin != bin || td.elem_base != ld.elem_offset + e) return 103;
+            if (td.n_elems == 0 || td.n_elems > cap || td.n_bins == 0 || td.n_bins > kMaxTileBins) return 104;
+            if (td.n_bins != (td.n_elems + td.L_T - 1) / td.L_T) return 105;
+            if (td.aligned() != (td.elem_base % 4 == 0)) return 106;
+            if (td.magic != bin_magic(td.L_T)) return 107;
+            if (td.n_elems > 16384u) return 108;  // the multiply-shift bin index is checked below this
+            e += td.n_elems;
+            bin += td.n_bins;
+            if (i + 1 < ld.n_ctiles && td.n_elems % td.L_T != 0) return 109;  // only the last tile may end in a short bin
+        }
+        if (e != ld.n_elems || bin != ld.n_bins) return 110;
+    }
+    if (ct != p.n_ctiles) return 111;
+    // unpack tiles: cover each layer exactly, at most kUnpackTileElems each, whole bins inside one
+    // 64-bin chunk or a slice of one long bin
+    std::vector<uint64_t> covered(p.n_layers, 0);
+    for (uint32_t i = 0; i < p.n_utiles; ++i) {
+        const UTileDev &ut = p.utiles[i];
+        if (ut.layer() >= p.n_layers) return 120;
+        const LayerDev &ld = p.layers[ut.layer()];
+        if (ut.L_T != ld.L_T || ut.n_elems == 0 || ut.n_elems > kUnpackTileElems) return 121;
+        const uint64_t local = uint64_t(ut.first_bin) * ut.L_T + ut.idx_lo;
+        if (ut.elem_base != ld.elem_offset + local || local != covered[ut.layer()]) return 122;
+        covered[ut.layer()] += ut.n_elems;
+        if (ut.L_T <= kUnpackTileElems) {
+            if (ut.idx_lo != 0 || ut.n_bins == 0 || ut.n_bins > 64) return 123;
+            if ((ut.first_bin >> 6) != ((ut.first_bin + ut.n_bins - 1) >> 6)) return 124;
+            if (ut.n_bins != (ut.n_elems + ut.L_T - 1) / ut.L_T) return 125;
+        } else {
+            if (ut.n_bins != 1 || ut.idx_lo + ut.n_elems > ut.L_T) return 126;
+        }
+        if (ut.group_log2() < 3 || ut.group_log2() > 6) return 127;
+        if (ut.aligned() != (ut.elem_base % 4 == 0)) return 128;
+    }
+    for (uint32_t l = 0; l < p.n_layers; ++l)
+        if (covered[l] != p.layers[l].n_elems) return 129;
+    // groups: consecutive tiles, every tile in exactly one group, at most kUnpackGroupTiles, all in
+    // one layer and one chunk (or one long bin): the kernel's table rows stay below 64
+    std::vector<uint8_t> seen(p.n_utiles, 0);
+    for (const UGroupDev &g : p.ugroups) {
+        if (g.n_tiles == 0 || g.n_tiles > kUnpackGroupTiles || uint64_t(g.first_tile) + g.n_tiles > p.n_utiles) return 130;
+        const UTileDev &a = p.utiles[g.first_tile];
+        for (uint32_t i = 0; i < g.n_tiles; ++i) {
+            const UTileDev &ut = p.utiles[g.first_tile + i];
+            if (seen[g.first_tile + i]++) return 131;
+            if (ut.layer() != a.layer()) return 132;
+            if (ut.L_T <= kUnpackTileElems ? (ut.first_bin >> 6) != (a.first_bin >> 6) : ut.first_bin != a.first_bin) return 133;
+            if (ut.first_bin < a.first_bin || ut.first_bin + ut.n_bins - a.first_bin > 64) return 134;
+        }
+    }
+    for (uint32_t i = 0; i < p.n_utiles; ++i)
+        if (seen[i] != 1) return 135;
+    std::fill(seen.begin(), seen.end(), 0);
+    for (const UGroupDev &g : p.usingles) {
+        if (g.n_tiles != 1 || g.first_tile >= p.n_utiles || seen[g.first_tile]++) return 136;
+    }
+    // workspace layout: sections in order, inside the advertised size
+    const WorkspaceLayout &w = p.ws;
+    if (!(w.layers < w.ctiles && w.ctiles <= w.utiles && w.utiles <= w.ugroups && w.ugroups <= w.usingles && w.usingles <= w.scratch)) return 140;
+    if (w.usingles + sizeof(UGroupDev) * size_t(p.n_utiles) > w.scratch) return 141;
+    if (w.stage + 2 * size_t(p.elem_span) + 32 > w.scratch_stride) return 142;
+    if (w.total(3) != adacomp_workspace_bytes_batch(t.data(), uint32_t(t.size()), 3)) return 143;
+    g_tiles_checked += p.n_ctiles + p.n_utiles;
+    g_groups_checked += p.n_ugroups;
+    return 0;
+}
 
 int main()
 {
@@ -31,6 +123,11 @@ int main()
         size_t goff = 0, gn = 0, gstride = 0;
         if (adacomp_workspace_gmax(t.data(), n_layers, &goff, &gn, &gstride) != ADACOMP_OK || goff + 4 * gn > ws1) return 3;
         checksum += bound + fixed + ws1 + gn;
+        // tile tables, with the default grouping of unpack tiles and with runs forced on small tables
+        adacomp_tuning_unpack_min_groups(rep % 2 ? 1u : 0u);
+        const int pc = check_plan(t);
+        adacomp_tuning_unpack_min_groups(0);
+        if (pc) { std::printf("plan check failed with %d at rep %d\n", pc, rep); return pc; }
         // calls on a workspace that was never initialised return before touching any device
         alignas(256) static char fake[4096];
         const float *g = reinterpret_cast<const float *>(fake);
@@ -48,8 +145,21 @@ int main()
         if (adacomp_packet_bound(b.data(), n_layers) != 0) return 7;
         if (n_layers > 1) { b = t; b[1].elem_offset = b[0].elem_offset; if (adacomp_packet_bound(b.data(), n_layers) != 0) return 8; }
     }
+    {   // the 125 M-element table of the benchmark: runs of 8 tiles that shorten towards the end
+        std::vector<adacomp_layer_t> t(7);
+        uint64_t off = 0;
+        for (int l = 0; l < 7; ++l) { t[l] = adacomp_layer_t{off, l < 6 ? 4096ull * 4096 : 4096ull * 5999, 500, 0}; off += t[l].n_elems; }
+        const int pc = check_plan(t);
+        if (pc) { std::printf("plan check of the large table failed with %d\n", pc); return pc; }
+        adacomp::Plan p;
+        adacomp::build_plan(t.data(), 7, true, p);
+        uint32_t longest = 0;
+        for (const auto &g : p.ugroups) longest = g.n_tiles > longest ? g.n_tiles : longest;
+        if (longest != adacomp::kUnpackGroupTiles || p.ugroups.back().n_tiles != 1) return 11;
+    }
     if (adacomp_selftest_binindex() != 0) return 9;
     for (int c = 1; c > -9; --c) if (!adacomp_strerror(c)) return 10;
-    std::printf("api sanitizer driver ok, checksum %llu\n", (unsigned long long)checksum);
+    std::printf("api sanitizer driver ok, checksum %llu, %llu tiles and %llu groups checked\n", (unsigned long long)checksum,
+                (unsigned long long)g_tiles_checked, (unsigned long long)g_groups_checked);
     return 0;
 }

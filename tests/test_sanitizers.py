@@ -23,6 +23,7 @@ def test_oracle_under_asan_ubsan(tmp_path):
     res = subprocess.run([str(exe)], capture_output=True, text=True, env=ENV, timeout=300)
     assert res.returncode == 0, res.stdout + res.stderr
     assert "driver ok" in res.stdout
+    print(res.stdout.strip())
 
 
 def test_library_host_code_under_asan_ubsan(tmp_path):
@@ -42,3 +43,4 @@ def test_library_host_code_under_asan_ubsan(tmp_path):
     res = subprocess.run([str(exe)], capture_output=True, text=True, env=ENV, timeout=300)
     assert res.returncode == 0, res.stdout + res.stderr
     assert "driver ok" in res.stdout
+    print(res.stdout.strip())
