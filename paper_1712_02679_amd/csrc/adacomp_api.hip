@@ -123,6 +123,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         ld.ctile_start = uint32_t(n_ctiles);
         ld.n_ctiles = nt;
         p.has_class[cls] = true;
+        if (T <= 64u) p.has_short_bins = true;
         if (tables) {
             for (uint32_t t = 0; t < nt; ++t) {
                 TileDev td;
@@ -246,7 +247,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     w.gmax = off;        off = pad256(off + 4 * size_t(p.n_bins_total));
     w.chunk_rel = off;   off = pad256(off + 4 * size_t(p.n_chunks_total));
     if (off >= (size_t(1) << 32)) return ADACOMP_EINVAL;
-    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span) + 64);  // slack: k_place reads 16 entries ahead
+    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span) + 128);  // slack: k_place reads up to 64 entries from a tile's start
     w.scratch_stride = off;
     return ADACOMP_OK;
 }
@@ -272,6 +273,7 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
     for (int c = 0; c < 3; ++c) out.has_class[c] = p.has_class[c];
+    out.has_short_bins = p.has_short_bins;
     out.table_hash = p.table_hash; out.ws = p.ws;
     return ADACOMP_OK;
 }
@@ -399,6 +401,7 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
     a.keep_gmax = g_keep_gmax ? 1u : 0u;
+    a.place_lanes = p.has_short_bins ? 64u : 16u;
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;

@@ -102,6 +102,7 @@ struct Plan {
     uint64_t fixed_bytes = 0;   // packet bytes before the first word
     uint64_t bound_bytes = 0;   // packet bytes with every element sent
     bool has_class[3] = {false, false, false};
+    bool has_short_bins = false;  // some layer has L_T <= 64 (8-bit words, many words per tile)
     uint64_t table_hash = 0;
     WorkspaceLayout ws;
     std::vector<LayerDev> layers;
@@ -128,6 +129,7 @@ struct CompressArgs {
     uint32_t o_tile_out, o_layer_nsel, o_layer_scale, o_gmax, o_chunk_rel;
     uint32_t n_tiles, n_layers, n_learners, keep_gmax;
     uint32_t fused_first, fused_count;  // learners covered by one k_fused launch
+    uint32_t place_lanes;               // lanes per tile in k_place: 16 or 64
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2
     uint64_t o_stage;

@@ -93,7 +93,7 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
     const WorkspaceLayout &w = p.ws;
     if (!(w.layers < w.ctiles && w.ctiles <= w.utiles && w.utiles <= w.ugroups && w.ugroups <= w.usingles && w.usingles <= w.scratch)) return 140;
     if (w.usingles + sizeof(UGroupDev) * size_t(p.n_utiles) > w.scratch) return 141;
-    if (w.stage + 2 * size_t(p.elem_span) + 32 > w.scratch_stride) return 142;
+    if (w.stage + 2 * size_t(p.elem_span) + 128 > w.scratch_stride) return 142;  // k_place reads 64 entries from a tile's start
     if (w.total(3) != adacomp_workspace_bytes_batch(t.data(), uint32_t(t.size()), 3)) return 143;
     g_tiles_checked += p.n_ctiles + p.n_utiles;
     g_groups_checked += p.n_ugroups;
