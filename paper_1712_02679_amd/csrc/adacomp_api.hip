@@ -224,6 +224,10 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         for (uint32_t i = 0; i < p.n_utiles; ++i)
             p.usingles[i] = UGroupDev{i < whole ? ((i & ~63u) | ((i & 7u) << 3) | ((i >> 3) & 7u)) : i, 1u};
         if (run_max == 1u) p.ugroups = p.usingles;
+        // groups of 8-bit layers first: the two kinds go to different kernels
+        auto is8 = [&p](const UGroupDev &g) { return p.utiles[g.first_tile].L_T <= 64u; };
+        p.n_ugroups8 = uint32_t(std::stable_partition(p.ugroups.begin(), p.ugroups.end(), is8) - p.ugroups.begin());
+        p.n_usingles8 = uint32_t(std::stable_partition(p.usingles.begin(), p.usingles.end(), is8) - p.usingles.begin());
         p.n_ugroups = uint32_t(p.ugroups.size());
     }
     p.n_bins_total = uint32_t(bins_total);
@@ -268,7 +272,7 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     if (p.n_layers != n_layers || p.table_hash != hash_table(layers, n_layers)) return ADACOMP_EWORKSPACE;
     if (workspace_bytes < p.ws.total(n_learners) || it->second.bytes < p.ws.total(n_learners)) return ADACOMP_EWORKSPACE;
     // copy the scalars only; the tables already live on the device
-    out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles; out.n_ugroups = p.n_ugroups;
+    out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles; out.n_ugroups = p.n_ugroups; out.n_ugroups8 = p.n_ugroups8; out.n_usingles8 = p.n_usingles8;
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
@@ -505,12 +509,24 @@ static int unpack_common(const adacomp_layer_t *layers, uint32_t n_layers, const
         a.accumulate = done > 0;
         a.mode = (opt && last) ? opt->kind : 0u;
         a.write_dense = dense_out != nullptr;
-        // runs of tiles per workgroup for the plain sum, single tiles when the optimizer step follows
-        a.groups = reinterpret_cast<const UGroupDev *>(ws + (a.mode == 0u ? p.ws.ugroups : p.ws.usingles));
-        a.n_groups = a.mode == 0u ? p.n_ugroups : p.n_utiles;
         for (uint32_t k = 0; k < kMaxPacketArgs; ++k)
             a.packets[k] = k < now ? static_cast<const uint8_t *>(packets[done + k]) : nullptr;
-        if ((rc = launch_unpack(a, hip_stream)) != ADACOMP_OK) return rc;
+        // runs of tiles per workgroup for the plain sum, single tiles when the optimizer step follows
+        const UGroupDev *table = reinterpret_cast<const UGroupDev *>(ws + (a.mode == 0u ? p.ws.ugroups : p.ws.usingles));
+        const uint32_t n_all = a.mode == 0u ? p.n_ugroups : p.n_utiles, n8 = a.mode == 0u ? p.n_ugroups8 : p.n_usingles8;
+        a.groups = table;
+        a.n_groups = n_all;
+        if (n8 == 0u || n8 == n_all) {  // one word width
+            if ((rc = launch_unpack(a, n8 ? 1 : 0, hip_stream)) != ADACOMP_OK) return rc;
+        } else if (p.n_utiles <= kUnpackSplitTiles) {  // small and mixed: one launch that handles both
+            if ((rc = launch_unpack(a, 2, hip_stream)) != ADACOMP_OK) return rc;
+        } else {  // large and mixed: the 8-bit groups come first in the table
+            a.n_groups = n8;
+            if ((rc = launch_unpack(a, 1, hip_stream)) != ADACOMP_OK) return rc;
+            a.groups = table + n8;
+            a.n_groups = n_all - n8;
+            if ((rc = launch_unpack(a, 0, hip_stream)) != ADACOMP_OK) return rc;
+        }
         done += now;
     } while (done < n_learners);
     return ADACOMP_OK;

@@ -536,13 +536,19 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 // a pass that only clears and writes the tiles takes 88 us, phase 1 per tile added 79 us and
 // phase 2 adds 63 us; sharing phase 1 over a run brought the whole launch from 230-250 to 185 us.
 // ==============================================================================================
+// Row strides of the two LDS tables.  With the natural strides (16 words, 8 words) the 64 lanes of
+// phase 1, which write one row each, would hit 2 and 4 of the 32 banks; 20 and 12 words spread
+// them over 8 banks and keep the rows 16-byte aligned for the wide reads of phase 2.
+constexpr uint32_t kOffStride = 20;  // uint32 per row, 16 used
+constexpr uint32_t kCntStride = 24;  // uint16 per row, 16 used
+
 // Phase 1 for learners k0 .. k0 + 15 and the bins [row0_bin, scan_end) of one 64-bin chunk: word
 // count and position of the first word of every (bin, learner), into the LDS tables (row = bin -
 // row0_bin).  The caller has a barrier before (the tables are free) and after (they are filled).
 template <bool W8>
 __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDev &ld, const uint32_t layer,
                                               const uint32_t row0_bin, const uint32_t scan_end, const uint32_t k0,
-                                              uint32_t (*s_off)[kLearnerGroup], uint16_t (*s_cnt)[kLearnerGroup],
+                                              uint32_t (*s_off)[kOffStride], uint16_t (*s_cnt)[kCntStride],
                                               float *s_scale, uint32_t *s_cmax)
 {
     typedef typename std::conditional<W8, uint8_t, uint16_t>::type word_t;
@@ -601,25 +607,76 @@ __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDe
 // Phase 2 for one tile: a lane group owns a bin (table row row0 + bin index inside the tile).
 template <bool W8>
 __device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev &ut, const uint32_t row0, const uint32_t k0,
-                                            float *s_acc, uint32_t (*s_off)[kLearnerGroup],
-                                            uint16_t (*s_cnt)[kLearnerGroup], const float *s_scale, const uint32_t *s_cmax)
+                                            float *s_acc, uint32_t (*s_off)[kOffStride],
+                                            uint16_t (*s_cnt)[kCntStride], const float *s_scale, const uint32_t *s_cmax)
 {
     typedef typename std::conditional<W8, uint8_t, uint16_t>::type word_t;
     const uint32_t tid = threadIdx.x;
     const uint32_t n = ut.n_elems, T = ut.L_T, nb = ut.n_bins;
     const uint32_t nk = a.n_learners - k0 < kLearnerGroup ? a.n_learners - k0 : kLearnerGroup;
+    if (W8) {
+        // Short bins (8-bit words) send several words each, about 8 % of the elements on the
+        // ResNet-50 table.  Four lanes own a bin and lane j fetches the aligned 4 bytes number j of
+        // the bin's run of words, for all 16 learners at once (16 words per bin and learner; longer
+        // runs are finished with byte loads), then adds learner after learner in program order.
+        const uint32_t lb = tid >> 2, sub = tid & 3u;
+        if (lb >= nb) return;
+        const uint32_t row = row0 + lb;
+        const uint32_t span = T < n - lb * T ? T : n - lb * T;  // elements of this bin held by the tile
+        float *acc = s_acc + lb * T;
+        // 8 learners at a time, to keep the register count (and with it the number of resident
+        // workgroups) where the 16-bit path has it
+#pragma unroll 1
+        for (uint32_t h0 = 0; h0 < kLearnerGroup; h0 += 8u) {
+            if (h0 >= nk) break;
+            uint32_t cc[8], off[8], packed[8];
+            {
+                const uint4 t = *reinterpret_cast<const uint4 *>(&s_cnt[row][h0]);
+                cc[0] = t.x & 0xFFFFu; cc[1] = t.x >> 16; cc[2] = t.y & 0xFFFFu; cc[3] = t.y >> 16;
+                cc[4] = t.z & 0xFFFFu; cc[5] = t.z >> 16; cc[6] = t.w & 0xFFFFu; cc[7] = t.w >> 16;
+                const uint4 o0 = *reinterpret_cast<const uint4 *>(&s_off[row][h0]);
+                const uint4 o1 = *reinterpret_cast<const uint4 *>(&s_off[row][h0 + 4u]);
+                off[0] = o0.x; off[1] = o0.y; off[2] = o0.z; off[3] = o0.w;
+                off[4] = o1.x; off[5] = o1.y; off[6] = o1.z; off[7] = o1.w;
+            }
+#pragma unroll
+            for (uint32_t kk = 0; kk < 8u; ++kk) {
+                packed[kk] = 0u;
+                // word sections start on 16-byte boundaries and are padded to them, so the aligned
+                // 4 bytes around any word of the run lie inside the packet
+                if (4u * sub < (off[kk] & 3u) + cc[kk])
+                    packed[kk] = reinterpret_cast<const uint32_t *>(a.packets[k0 + (h0 + kk < nk ? h0 + kk : 0u)])[(off[kk] >> 2) + sub];
+            }
+#pragma unroll
+            for (uint32_t kk = 0; kk < 8u; ++kk) {
+                __builtin_amdgcn_sched_barrier(0);  // one learner at a time: keeps the register count down
+                const uint32_t skew = off[kk] & 3u, cck = cc[kk];
+                const float sck = s_scale[h0 + kk];
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j) {
+                    const uint32_t at = 4u * sub + j;  // byte of the fetched 16
+                    const uint32_t wd = (packed[kk] >> (8u * j)) & 0xFFu;
+                    const uint32_t idx = wd >> 2, code = wd & 3u;
+                    if (at >= skew && at - skew < cck && (code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
+                }
+                if (skew + cck > 16u) {  // the words of this learner beyond the fetched 16 bytes
+                    const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + (h0 + kk < nk ? h0 + kk : 0u)]);
+                    for (uint32_t q = 16u - skew + sub; q < cck; q += 4u) {
+                        const uint32_t wd = wp[off[kk] + q];
+                        const uint32_t idx = wd >> 2, code = wd & 3u;
+                        if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
+                    }
+                }
+            }
+        }
+        return;
+    }
     // lanes per bin: the smallest power of two that holds the largest word count of the tables,
     // between the layer's default (8 or 16) and the whole wave
     uint32_t glog = ut.group_log2();
     while (glog < 6u && (1u << glog) < *s_cmax) ++glog;
     const uint32_t gsz = 1u << glog;
 
-    float scl[kLearnerGroup];
-#pragma unroll
-    for (uint32_t v = 0; v < kLearnerGroup / 4u; ++v) {
-        const float4 t = *reinterpret_cast<const float4 *>(&s_scale[4u * v]);
-        scl[4 * v] = t.x; scl[4 * v + 1] = t.y; scl[4 * v + 2] = t.z; scl[4 * v + 3] = t.w;
-    }
     for (uint32_t s = tid; s < (nb << glog); s += kWG) {
         const uint32_t lb = s >> glog, sub = s & (gsz - 1u);
         const uint32_t row = row0 + lb;
@@ -653,7 +710,7 @@ __device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev 
             for (uint32_t kk = 0; kk < kLearnerGroup; ++kk) {
                 const uint32_t idx = (word[kk] >> 2) - ut.idx_lo;  // wraps to a huge value below idx_lo
                 const uint32_t code = word[kk] & 3u;
-                if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? scl[kk] : -scl[kk]);
+                if ((code & 1u) && idx < span) { const float sck = s_scale[kk]; atomicAdd(&acc[idx], code == 1u ? sck : -sck); }
             }
         } else {
             // some learner sends more words from this bin than the group has lanes: plain loops,
@@ -704,8 +761,14 @@ __device__ __forceinline__ void apply_update(const UnpackArgs &a, float sum, flo
 }
 
 // MODE 0: dense_out <- sum.  MODE 1 / 2: also (or only) the SGD / Adam step on weights and state.
-template <int MODE>
-__global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
+// KIND 0 / 1: all groups of this launch belong to layers with 16-bit / 8-bit words; 2: either (the
+// layer says which).  Large tables get one launch per kind: each path alone needs fewer registers
+// than a kernel that holds both, which buys resident workgroups (8 % of the 16-bit path's time on
+// the 125 M-element table).  Small tables, where a second launch would cost more than that, use
+// the kernel that holds both.  The single-width kernels are held to 80 registers (6 waves per
+// SIMD, what the LDS tile allows; the 16-bit path spills two).
+template <int MODE, int KIND>
+__global__ __launch_bounds__(kWG, (KIND == 2 ? 4 : 6)) void k_unpack(const UnpackArgs a)
 {
     // A workgroup serves a group of consecutive tiles that lie in one 64-bin chunk (or are slices
     // of one long bin).  With up to 16 learners the tables of phase 1 are built once for the group.
@@ -718,11 +781,11 @@ __global__ __launch_bounds__(kWG) void k_unpack(const UnpackArgs a)
     const uint32_t tid = threadIdx.x;
     const uint32_t row0_bin = ut0.first_bin, scan_end = ut_last.first_bin + ut_last.n_bins;
     const bool tables_once = a.n_learners <= kLearnerGroup;
-    const bool w8 = ld.word_bytes == 1u;
+    const bool w8 = KIND == 2 ? ld.word_bytes == 1u : KIND == 1;
 
     __shared__ float s_acc[kUnpackTileElems];
-    __shared__ __attribute__((aligned(16))) uint32_t s_off[64][kLearnerGroup];  // first word of (bin, learner), counted from the packet start
-    __shared__ __attribute__((aligned(16))) uint16_t s_cnt[64][kLearnerGroup];
+    __shared__ __attribute__((aligned(16))) uint32_t s_off[64][kOffStride];  // first word of (bin, learner), counted from the packet start
+    __shared__ __attribute__((aligned(16))) uint16_t s_cnt[64][kCntStride];
     __shared__ __attribute__((aligned(16))) float s_scale[kLearnerGroup];
     __shared__ uint32_t s_cmax;                                                // largest word count of a (bin, learner) in the tables
 
@@ -845,12 +908,24 @@ int launch_place(const CompressArgs &a, void *stream)
     return check_launch();
 }
 
-int launch_unpack(const UnpackArgs &a, void *stream)
+int launch_unpack(const UnpackArgs &a, int kind, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (a.mode == 1) hipLaunchKernelGGL(k_unpack<1>, dim3(a.n_groups), dim3(kWG), 0, s, a);
-    else if (a.mode == 2) hipLaunchKernelGGL(k_unpack<2>, dim3(a.n_groups), dim3(kWG), 0, s, a);
-    else hipLaunchKernelGGL(k_unpack<0>, dim3(a.n_groups), dim3(kWG), 0, s, a);
+    if (a.n_groups == 0) return ADACOMP_OK;
+    const dim3 grid(a.n_groups), wg(kWG);
+    if (kind == 1) {
+        if (a.mode == 1) hipLaunchKernelGGL((k_unpack<1, 1>), grid, wg, 0, s, a);
+        else if (a.mode == 2) hipLaunchKernelGGL((k_unpack<2, 1>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_unpack<0, 1>), grid, wg, 0, s, a);
+    } else if (kind == 0) {
+        if (a.mode == 1) hipLaunchKernelGGL((k_unpack<1, 0>), grid, wg, 0, s, a);
+        else if (a.mode == 2) hipLaunchKernelGGL((k_unpack<2, 0>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_unpack<0, 0>), grid, wg, 0, s, a);
+    } else {
+        if (a.mode == 1) hipLaunchKernelGGL((k_unpack<1, 2>), grid, wg, 0, s, a);
+        else if (a.mode == 2) hipLaunchKernelGGL((k_unpack<2, 2>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_unpack<0, 2>), grid, wg, 0, s, a);
+    }
     return check_launch();
 }
 

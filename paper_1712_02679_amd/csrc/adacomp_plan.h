@@ -68,6 +68,7 @@ struct UGroupDev {
 static_assert(sizeof(UGroupDev) == 8, "UGroupDev layout");
 constexpr uint32_t kUnpackGroupTiles = 8;   // at most this many tiles per group
 constexpr uint32_t kUnpackMinGroups = 2048;  // groups of more than one tile only while this many workgroups remain (8 per compute unit)
+constexpr uint32_t kUnpackSplitTiles = 2048;  // tables with both word widths and more tiles than this: one launch per width
 constexpr uint32_t kUnpackTaperTiles = 768;  // tiles at the end of the table that go alone (3 per compute unit)
 
 // What k_fused leaves per tile for k_scan and k_place: one 16-byte record, so that a tile makes one
@@ -96,6 +97,7 @@ struct WorkspaceLayout {
 struct Plan {
     uint32_t n_layers = 0;
     uint32_t n_ctiles = 0, n_utiles = 0, n_ugroups = 0;
+    uint32_t n_ugroups8 = 0, n_usingles8 = 0;  // groups of layers with 8-bit words: they come first in both tables
     uint32_t n_bins_total = 0, n_chunks_total = 0;
     uint64_t elem_span = 0;     // max over layers of elem_offset + n_elems
     uint64_t n_elems_total = 0;
@@ -158,7 +160,7 @@ struct UnpackArgs {
 int launch_fused(const CompressArgs &a, int jcode, void *stream);
 int launch_scan(const CompressArgs &a, void *stream);
 int launch_place(const CompressArgs &a, void *stream);
-int launch_unpack(const UnpackArgs &a, void *stream);
+int launch_unpack(const UnpackArgs &a, int kind, void *stream);  // kind 0: 16-bit words, 1: 8-bit, 2: both
 int launch_copy(float *dst, const float *src, size_t n, void *stream);
 
 }  // namespace adacomp

@@ -85,6 +85,12 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
     }
     for (uint32_t i = 0; i < p.n_utiles; ++i)
         if (seen[i] != 1) return 135;
+    // both tables list the groups of layers with 8-bit words first (they go to their own kernel)
+    if (p.n_ugroups8 > p.n_ugroups || p.n_usingles8 > p.n_utiles) return 137;
+    for (uint32_t i = 0; i < p.n_ugroups; ++i)
+        if ((p.utiles[p.ugroups[i].first_tile].L_T <= 64u) != (i < p.n_ugroups8)) return 138;
+    for (uint32_t i = 0; i < p.n_utiles; ++i)
+        if ((p.utiles[p.usingles[i].first_tile].L_T <= 64u) != (i < p.n_usingles8)) return 139;
     std::fill(seen.begin(), seen.end(), 0);
     for (const UGroupDev &g : p.usingles) {
         if (g.n_tiles != 1 || g.first_tile >= p.n_utiles || seen[g.first_tile]++) return 136;
