@@ -175,7 +175,11 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
 
 /* packets    HOST array of n_learners DEVICE pointers to complete packets made by
  *            adacomp_compress with the same layer table.  A packet whose header does not match
- *            (magic, version, status, n_layers) contributes nothing.
+ *            (magic, version, status, n_layers) contributes nothing.  The counts and offsets
+ *            inside a packet are otherwise taken as they are; the only check is that no word is
+ *            read at or beyond the header's total_bytes (a bin whose words would lie there
+ *            contributes nothing), so the buffer must hold total_bytes bytes.  Whatever a
+ *            packet holds, nothing outside dense_out is written.
  * dense_out  every element of every layer is overwritten with the float32 sum, taken in learner
  *            order 0..n-1, of the decoded values (+-scale of that learner's layer where it sent
  *            the element, 0 elsewhere); 16-byte aligned.  n_learners == 0 writes zeros.

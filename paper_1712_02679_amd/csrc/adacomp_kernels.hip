@@ -565,18 +565,20 @@ __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDe
     __syncthreads();
 
     // wave w serves learners w, w + 4, ...; all their loads are issued first
-    uint32_t c[kPerWave], coff[kPerWave], wbase[kPerWave];
+    uint32_t c[kPerWave], coff[kPerWave], wbase[kPerWave], limit[kPerWave];
     float sc[kPerWave];
     bool ok[kPerWave];
 #pragma unroll
     for (uint32_t q = 0; q < kPerWave; ++q) {
         const uint32_t kk = wave + 4u * q;
-        c[q] = 0u; coff[q] = 0u; wbase[q] = 0u; sc[q] = 0.f; ok[q] = false;
+        c[q] = 0u; coff[q] = 0u; wbase[q] = 0u; limit[q] = 0u; sc[q] = 0.f; ok[q] = false;
         if (kk < nk) {
             const uint8_t *pk = a.packets[k0 + kk];
             const uint4 hv = *reinterpret_cast<const uint4 *>(pk);  // magic, version, status, n_layers
+            const uint2 tb = *reinterpret_cast<const uint2 *>(pk + 16);  // total_bytes
             ok[q] = (hv.x == ADACOMP_PACKET_MAGIC) & (hv.y == ADACOMP_PACKET_VERSION) &
-                    (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers);
+                    (hv.z == ADACOMP_STATUS_COMPLETE) & (hv.w == a.n_layers) & (tb.y == 0u);
+            limit[q] = tb.x / uint32_t(sizeof(word_t));  // words that fit in the packet
             // counts and chunk offsets sit in the fixed part, which every packet buffer holds
             if (in_scan) c[q] = reinterpret_cast<const word_t *>(pk + ld.counts_offset)[b];
             coff[q] = reinterpret_cast<const uint32_t *>(pk + ld.chunks_offset)[chunk];
@@ -592,12 +594,17 @@ __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDe
         const uint32_t kk = wave + 4u * q;  // < kLearnerGroup; learners past nk get empty entries
         const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
         const uint32_t incl = wave_incl_scan(cq, lane);
+        // A bin whose words would lie past the packet's total_bytes (counts or offsets that do not
+        // belong together) contributes nothing: no word is read from outside the packet.
+        const uint64_t first = uint64_t(wbase[q]) + coff[q] + (incl - cq);
+        const bool inside = first + cq <= limit[q];
+        const uint32_t cw = inside ? cq : 0u;
         if (in_rows) {
-            s_off[b - row0_bin][kk] = wbase[q] + coff[q] + incl - cq;
-            s_cnt[b - row0_bin][kk] = uint16_t(cq);
+            s_off[b - row0_bin][kk] = inside ? uint32_t(first) : 0u;
+            s_cnt[b - row0_bin][kk] = uint16_t(cw);
         }
         if (lane == 0) s_scale[kk] = sc[q];
-        wmax = (in_rows && cq > wmax) ? cq : wmax;
+        wmax = (in_rows && cw > wmax) ? cw : wmax;
     }
 #pragma unroll
     for (uint32_t d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(wmax, d, 64); wmax = o > wmax ? o : wmax; }
@@ -644,7 +651,7 @@ __device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev 
                 packed[kk] = 0u;
                 // word sections start on 16-byte boundaries and are padded to them, so the aligned
                 // 4 bytes around any word of the run lie inside the packet
-                if (4u * sub < (off[kk] & 3u) + cc[kk])
+                if (cc[kk] != 0u && 4u * sub < (off[kk] & 3u) + cc[kk])
                     packed[kk] = reinterpret_cast<const uint32_t *>(a.packets[k0 + (h0 + kk < nk ? h0 + kk : 0u)])[(off[kk] >> 2) + sub];
             }
 #pragma unroll

@@ -444,6 +444,40 @@ def test_truncated_packet(H, oracle_lib):
     assert e.value.code == -4
 
 
+@pytest.mark.parametrize("T", [50, 500])
+def test_unpack_bins_past_total_bytes_contribute_nothing(H, oracle_lib, T):
+    """A packet whose chunk offset points past its own total_bytes: the bins of that chunk are
+    dropped for that learner, everything else is summed as usual, and no word is read from beyond
+    total_bytes (the altered offset still points inside the allocated buffer, which is as long as
+    the packet bound, so this holds whatever the kernel does)."""
+    import gpu_harness as G
+    import packet_format as pf
+    wl = W.custom("past_end", [("a", T * 64 * 3 + 7, T)])
+    table, n = wl.table(), wl.n_total
+    gpu = G.GpuSide(table, n, 3)
+    try:
+        cpu_packets = []
+        for k in range(3):
+            g = W.gradient(wl, k, 0)
+            cpu_packets.append(oracle_lib.compress(table, g, np.zeros(n, f32)))
+            gpu.compress(k, g)
+        h, layers = pf.parse(cpu_packets[1])
+        word_bytes = int(layers[0]["rec"]["word_bits"]) // 8
+        cho = int(layers[0]["rec"]["chunks_offset"])
+        past = int(h["total_bytes"]) // word_bytes + 1000              # in words, counted from the layer's first word
+        assert (int(layers[0]["rec"]["words_offset"]) + (past + 64 * T) * word_bytes) < gpu.capacity
+        altered = torch.tensor(np.array([past], "<u4").view(np.uint8), device=G.DEV)
+        gpu.packets[1][cho + 4:cho + 8] = altered                      # chunk 1 of learner 1
+        got = gpu.unpack([0, 1, 2])
+        want = oracle_lib.unpack_accumulate(table, cpu_packets, n)
+        without = oracle_lib.unpack_accumulate(table, [cpu_packets[0], cpu_packets[2]], n)
+        lo, hi = 64 * T, 128 * T
+        want[lo:hi] = without[lo:hi]
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    finally:
+        gpu.close()
+
+
 def test_many_learners(H, oracle_lib):
     """0, 1, 17 and 70 learners: empty sum, learner groups of 16 in LDS, more than one launch of 64."""
     import gpu_harness as G
