@@ -265,7 +265,7 @@ def test_variant_default_equals_compress(H):
 # ------------------------------------------------------------------------------------------------
 # unpack + average + optimizer step in one pass
 # ------------------------------------------------------------------------------------------------
-def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0):
+def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0, threads=1):
     import gpu_harness as G
     import paper_1712_02679_amd as A
     table, n = wl.table(), wl.n_total
@@ -281,9 +281,14 @@ def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0):
     try:
         for t in range(n_steps):
             G.say(f"{wl.name} update kind {kind} step {t}")
-            grads = [W.gradient(wl, k, t, seed=seed) for k in range(n_learners)]
+            grads = [W.gradient(wl, k, t, seed=seed, threads=threads) for k in range(n_learners)]
             gpu.compress_batch(grads)
-            pk_cpu = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(n_learners)]
+            if threads > 1:  # learners are independent: one oracle call per host thread
+                from concurrent.futures import ThreadPoolExecutor
+                with ThreadPoolExecutor(min(threads, n_learners)) as pool:
+                    pk_cpu = list(pool.map(lambda k: oracle_lib.compress(table, grads[k], R_cpu[k]), range(n_learners)))
+            else:
+                pk_cpu = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(n_learners)]
             dense_cpu = oracle_lib.unpack_accumulate(table, pk_cpu, n)
             dense_cpu[~mask] = 0
             bias1, bias2 = float(f32(1 - b1 ** (t + 1))), float(f32(1 - b2 ** (t + 1)))
@@ -313,6 +318,14 @@ def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0):
 @pytest.mark.parametrize("kind,with_dense", [(1, False), (1, True), (2, False), (2, True)])
 def test_unpack_update_workload2(H, oracle_lib, kind, with_dense):
     _update_case(oracle_lib, W.workload(2), 4, 6, kind, with_dense)
+
+
+def test_unpack_update_full_size_tables(H, oracle_lib):
+    """The launch configurations bench.py times: Adam on the 125 M-element table with 16 packets
+    (single tiles, 16-bit kernel) and SGD on the ResNet-50 table with 8 packets (one launch per
+    word width), each one step from zero residues, every element against the oracle."""
+    _update_case(oracle_lib, W.workload(5), 16, 1, 2, False, threads=16)
+    _update_case(oracle_lib, W.workload(3), 8, 1, 1, True, threads=16)
 
 
 @pytest.mark.parametrize("kind", [1, 2])
