@@ -23,25 +23,12 @@ uint32_t bin_magic(uint32_t L_T)
     return L_T <= 1 ? 0u : uint32_t((uint64_t(1) << 32) / L_T) + 1u;
 }
 
-int default_register_class()
-{
-    // Elements a thread keeps in registers: 16 * (1 << class).  Class 0 (tiles of 4096 elements)
-    // unless ADACOMP_TILE_CLASS says otherwise; larger bins force a larger class per layer.
-    static int cls = [] {
-        const char *e = std::getenv("ADACOMP_TILE_CLASS");
-        int v = e ? std::atoi(e) : 0;
-        return v < 0 ? 0 : (v > 2 ? 2 : v);
-    }();
-    return cls;
-}
-
 uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers)
 {
     uint64_t h = 1469598103934665603ull;  // FNV-1a over the fields that matter
     auto mix = [&h](uint64_t v) { for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xFF; h *= 1099511628211ull; } };
     mix(n_layers);
     for (uint32_t l = 0; l < n_layers; ++l) { mix(layers[l].elem_offset); mix(layers[l].n_elems); mix(layers[l].L_T); }
-    mix(uint64_t(default_register_class()));
     return h;
 }
 
@@ -86,7 +73,6 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     uint64_t fixed = sizeof(adacomp_packet_header_t) + uint64_t(sizeof(adacomp_packet_layer_t)) * n_layers;
     uint64_t words_bound = 0;
     uint64_t n_ctiles = 0, n_utiles = 0, bins_total = 0, chunks_total = 0;
-    const int base_cls = default_register_class();
 
     for (uint32_t l = 0; l < n_layers; ++l) {
         const uint32_t T = layers[l].L_T;
@@ -109,12 +95,12 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         p.elem_span = std::max<uint64_t>(p.elem_span, layers[l].elem_offset + n);
         p.n_elems_total += n;
 
-        // ---- compress tiles: whole bins, as many as fit the register class --------------------
-        // Tiles of 8192 elements (class 1) stream at less than half the rate of 4096 or 16384 on
-        // MI355X (measured on a plain triad), so bins above 4096 go straight to class 2.
-        int cls = base_cls;
-        if (T > (4096u << cls)) cls = 2;
-        const uint32_t cap = 4096u << cls;
+        // ---- compress tiles: whole bins, as many as fit the registers of a workgroup ------------
+        // 16 elements per thread (tiles of 4096 elements) unless a bin is longer: then 64 per thread
+        // (16384).  Tiles of 8192 elements streamed at less than half the rate of either on MI355X
+        // (measured on a plain triad), so there is no class in between.
+        const int cls = T > 4096u ? 1 : 0;
+        const uint32_t cap = cls ? 16384u : 4096u;
         uint32_t bpt = cap / T;                       // >= 1
         if (bpt > kMaxTileBins) bpt = kMaxTileBins;
         const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
@@ -122,7 +108,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         const uint32_t nt = (n_bins + bpt - 1) / bpt;
         ld.ctile_start = uint32_t(n_ctiles);
         ld.n_ctiles = nt;
-        p.has_class[cls] = true;
+        p.n_class_tiles[cls] += nt;
         if (T <= 64u) p.has_short_bins = true;
         if (tables) {
             for (uint32_t t = 0; t < nt; ++t) {
@@ -188,6 +174,13 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     }
     p.n_ctiles = uint32_t(n_ctiles);
     p.n_utiles = uint32_t(n_utiles);
+    if (tables && p.n_class_tiles[0] && p.n_class_tiles[1]) {
+        // both tile sizes: each gets its own k_fused launch over its own tiles
+        p.cclass.reserve(p.n_ctiles);
+        for (uint32_t c = 0; c < 2u; ++c)
+            for (uint32_t i = 0; i < p.n_ctiles; ++i)
+                if (p.ctiles[i].jcode() == c) p.cclass.push_back(i);
+    }
     if (tables) {
         // ---- unpack groups: runs of tiles that share phase 1 (same layer and 64-bin chunk, or the
         //      same long bin).  Longer runs save more table work but leave fewer workgroups, so the
@@ -240,6 +233,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     size_t off = 256;  // first 256 bytes: reserved
     w.layers = off;      off = pad256(off + sizeof(LayerDev) * size_t(n_layers));
     w.ctiles = off;      off = pad256(off + sizeof(TileDev) * size_t(p.n_ctiles));
+    w.cclass = off;      off = pad256(off + 4 * size_t(p.n_ctiles));
     w.utiles = off;      off = pad256(off + sizeof(UTileDev) * size_t(p.n_utiles));
     w.ugroups = off;     off = pad256(off + sizeof(UGroupDev) * size_t(p.n_utiles));  // at most one group per tile
     w.usingles = off;    off = pad256(off + sizeof(UGroupDev) * size_t(p.n_utiles));
@@ -276,7 +270,7 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
-    for (int c = 0; c < 3; ++c) out.has_class[c] = p.has_class[c];
+    for (int c = 0; c < 2; ++c) out.n_class_tiles[c] = p.n_class_tiles[c];
     out.has_short_bins = p.has_short_bins;
     out.table_hash = p.table_hash; out.ws = p.ws;
     return ADACOMP_OK;
@@ -353,12 +347,14 @@ int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, voi
     char *ws = static_cast<char *>(workspace);
     if (hipMemcpy(ws + p.ws.layers, p.layers.data(), sizeof(LayerDev) * p.layers.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ws + p.ws.ctiles, p.ctiles.data(), sizeof(TileDev) * p.ctiles.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        (!p.cclass.empty() && hipMemcpy(ws + p.ws.cclass, p.cclass.data(), 4 * p.cclass.size(), hipMemcpyHostToDevice) != hipSuccess) ||
         hipMemcpy(ws + p.ws.utiles, p.utiles.data(), sizeof(UTileDev) * p.utiles.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ws + p.ws.ugroups, p.ugroups.data(), sizeof(UGroupDev) * p.ugroups.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ws + p.ws.usingles, p.usingles.data(), sizeof(UGroupDev) * p.usingles.size(), hipMemcpyHostToDevice) != hipSuccess)
         return ADACOMP_EHIP;
     // the host copies of the tile tables are no longer needed
     p.ctiles.clear(); p.ctiles.shrink_to_fit();
+    p.cclass.clear(); p.cclass.shrink_to_fit();
     p.utiles.clear(); p.utiles.shrink_to_fit();
     p.ugroups.clear(); p.ugroups.shrink_to_fit();
     p.usingles.clear(); p.usingles.shrink_to_fit();
@@ -405,6 +401,7 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
     a.keep_gmax = g_keep_gmax ? 1u : 0u;
+    a.class_tiles = (p.n_class_tiles[0] && p.n_class_tiles[1]) ? reinterpret_cast<const uint32_t *>(ws + p.ws.cclass) : nullptr;
     a.place_lanes = p.has_short_bins ? 64u : 16u;
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
@@ -440,8 +437,12 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
                 g_timing.learners += a.fused_count;
                 if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
             }
-            for (int c = 0; c < 3; ++c)
-                if (p.has_class[c] && (rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
+            for (int c = 0; c < 2; ++c) {
+                if (p.n_class_tiles[c] == 0) continue;
+                a.class_first = c ? p.n_class_tiles[0] : 0u;
+                a.class_count = p.n_class_tiles[c];
+                if ((rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
+            }
             if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
         }
         if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;

@@ -90,17 +90,18 @@ template <int J, bool VARIANT>
 __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 {
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
-    // call streams one learner's buffers after the other instead of all of them at once
-    const uint32_t lq = blockIdx.x / a.n_tiles;
-    uint32_t tile = blockIdx.x - lq * a.n_tiles;
+    // call streams one learner's buffers after the other instead of all of them at once.  A launch
+    // covers the class_count tiles of one register class (all tiles, for most tables).
+    const uint32_t lq = blockIdx.x / a.class_count;
+    uint32_t pos = blockIdx.x - lq * a.class_count;
     const uint32_t lr = a.fused_first + lq;
     // Workgroups go to the 8 XCDs round-robin by index.  Inside each run of 64 the mapping is
     // transposed, so that the 8 workgroups landing on one XCD take 8 consecutive tiles (128 KB of
     // each stream): measured 6-9 % faster than the identity on a plain triad with these tiles,
     // and free of the slowdown of long launches.
-    if (tile < (a.n_tiles & ~63u)) tile = (tile & ~63u) | ((tile & 7u) << 3) | ((tile >> 3) & 7u);
+    if (pos < (a.class_count & ~63u)) pos = (pos & ~63u) | ((pos & 7u) << 3) | ((pos >> 3) & 7u);
+    const uint32_t tile = a.class_tiles ? a.class_tiles[a.class_first + pos] : pos;
     const TileDev td = a.tiles[tile];
-    if (td.jcode() != (J == 4 ? 0u : (J == 8 ? 1u : 2u))) return;
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
     float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
@@ -887,15 +888,13 @@ static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK 
 int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(a.n_tiles * a.fused_count), wg(kWG);
+    const dim3 grid(a.class_count * a.fused_count), wg(kWG);
     const bool variant = a.rule != ADACOMP_RULE_ADACOMP || a.soft_factor_minus_1 != 1.0f;
     if (!variant) {
         if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false>), grid, wg, 0, s, a);
-        else if (jcode == 1) hipLaunchKernelGGL((k_fused<8, false>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<16, false>), grid, wg, 0, s, a);
     } else {
         if (jcode == 0) hipLaunchKernelGGL((k_fused<4, true>), grid, wg, 0, s, a);
-        else if (jcode == 1) hipLaunchKernelGGL((k_fused<8, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<16, true>), grid, wg, 0, s, a);
     }
     return check_launch();

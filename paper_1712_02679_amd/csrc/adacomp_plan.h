@@ -33,14 +33,14 @@ static_assert(sizeof(LayerDev) == 64, "LayerDev layout");
 // One workgroup's share of adacomp_compress: whole bins of one layer (32 bytes).
 struct TileDev {
     uint64_t elem_base;   // first element in grad / residue (layer offset included)
-    uint32_t n_elems;     // elements in the tile, <= 1024 * J
+    uint32_t n_elems;     // elements in the tile, <= 4096 or 16384 by register class
     uint32_t L_T;
     uint32_t magic;       // floor(2^32 / L_T) + 1: bin = umulhi(e, magic) for e < 16384 (L_T > 1)
     uint32_t n_bins;      // bins in the tile, <= kMaxTileBins
     uint32_t first_bin;   // index of the tile's first bin inside the layer
-    uint32_t layer_flags; // bits 0..23 layer, 24..25 register class (0: J=4, 1: J=8, 2: J=16), bit 31 aligned
+    uint32_t layer_flags; // bits 0..23 layer, bit 24 register class (0: 4096-element tiles, 1: 16384), bit 31 aligned
     __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
-    __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 3u; }
+    __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 1u; }
     __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
 };
 static_assert(sizeof(TileDev) == 32, "TileDev layout");
@@ -83,7 +83,7 @@ static_assert(sizeof(TileOut) == 16, "TileOut layout");
 // Byte offsets inside the caller's workspace.  The tables come first; then one scratch block per
 // learner of a batched call (a single-learner call uses block 0).
 struct WorkspaceLayout {
-    size_t layers = 0, ctiles = 0, utiles = 0, ugroups = 0, usingles = 0;  // tables written by workspace_init
+    size_t layers = 0, ctiles = 0, cclass = 0, utiles = 0, ugroups = 0, usingles = 0;  // tables written by workspace_init
     size_t scratch = 0;                                 // first scratch block
     size_t scratch_stride = 0;                          // bytes per learner
     // offsets inside a scratch block
@@ -103,7 +103,8 @@ struct Plan {
     uint64_t n_elems_total = 0;
     uint64_t fixed_bytes = 0;   // packet bytes before the first word
     uint64_t bound_bytes = 0;   // packet bytes with every element sent
-    bool has_class[3] = {false, false, false};
+    uint32_t n_class_tiles[2] = {0, 0};  // compress tiles of 4096 / of 16384 elements
+    std::vector<uint32_t> cclass;        // compress tile indices, the 4096-element ones first (tables with both kinds)
     bool has_short_bins = false;  // some layer has L_T <= 64 (8-bit words, many words per tile)
     uint64_t table_hash = 0;
     WorkspaceLayout ws;
@@ -117,7 +118,6 @@ struct Plan {
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &plan);
 uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers);
 uint32_t bin_magic(uint32_t L_T);
-int default_register_class();
 
 // ---- kernel launchers (adacomp_kernels.hip) ---------------------------------------------------
 constexpr uint32_t kMaxBatch = 32;  // learners per launch of the compress kernels
@@ -131,6 +131,8 @@ struct CompressArgs {
     uint32_t o_tile_out, o_layer_nsel, o_layer_scale, o_gmax, o_chunk_rel;
     uint32_t n_tiles, n_layers, n_learners, keep_gmax;
     uint32_t fused_first, fused_count;  // learners covered by one k_fused launch
+    const uint32_t *class_tiles;        // tile indices by register class, or null: the launch covers tiles 0 .. class_count - 1
+    uint32_t class_first, class_count;  // this launch's stretch of class_tiles
     uint32_t place_lanes;               // lanes per tile in k_place: 16 or 64
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2

@@ -32,7 +32,7 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
         uint32_t bin = 0;
         for (uint32_t i = 0; i < ld.n_ctiles; ++i, ++ct) {
             const TileDev &td = p.ctiles[ct];
-            const uint32_t cap = 4096u << td.jcode();
+            const uint32_t cap = td.jcode() ? 16384u : 4096u;
             if (td.layer() != l || td.L_T != ld.L_T || td.first_bin != bin || td.elem_base != ld.elem_offset + e) return 103;
             if (td.n_elems == 0 || td.n_elems > cap || td.n_bins == 0 || td.n_bins > kMaxTileBins) return 104;
             if (td.n_bins != (td.n_elems + td.L_T - 1) / td.L_T) return 105;
@@ -46,6 +46,16 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
         if (e != ld.n_elems || bin != ld.n_bins) return 110;
     }
     if (ct != p.n_ctiles) return 111;
+    // tables with both tile sizes list the tile indices by size, each size in ascending order
+    if (p.n_class_tiles[0] + p.n_class_tiles[1] != p.n_ctiles) return 112;
+    if (p.n_class_tiles[0] && p.n_class_tiles[1]) {
+        if (p.cclass.size() != p.n_ctiles) return 113;
+        for (uint32_t i = 0; i < p.n_ctiles; ++i) {
+            const uint32_t want = i < p.n_class_tiles[0] ? 0u : 1u;
+            if (p.cclass[i] >= p.n_ctiles || p.ctiles[p.cclass[i]].jcode() != want) return 114;
+            if (i && i != p.n_class_tiles[0] && p.cclass[i] <= p.cclass[i - 1]) return 115;
+        }
+    } else if (!p.cclass.empty()) return 116;
     // unpack tiles: cover each layer exactly, at most kUnpackTileElems each, whole bins inside one
     // 64-bin chunk or a slice of one long bin
     std::vector<uint64_t> covered(p.n_layers, 0);
@@ -97,7 +107,8 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
     }
     // workspace layout: sections in order, inside the advertised size
     const WorkspaceLayout &w = p.ws;
-    if (!(w.layers < w.ctiles && w.ctiles <= w.utiles && w.utiles <= w.ugroups && w.ugroups <= w.usingles && w.usingles <= w.scratch)) return 140;
+    if (w.cclass + 4 * size_t(p.n_ctiles) > w.utiles) return 144;
+    if (!(w.layers < w.ctiles && w.ctiles <= w.cclass && w.cclass <= w.utiles && w.utiles <= w.ugroups && w.ugroups <= w.usingles && w.usingles <= w.scratch)) return 140;
     if (w.usingles + sizeof(UGroupDev) * size_t(p.n_utiles) > w.scratch) return 141;
     if (w.stage + 2 * size_t(p.elem_span) + 128 > w.scratch_stride) return 142;  // k_place reads 64 entries from a tile's start
     if (w.total(3) != adacomp_workspace_bytes_batch(t.data(), uint32_t(t.size()), 3)) return 143;
