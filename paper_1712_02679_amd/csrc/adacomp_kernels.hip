@@ -1,7 +1,9 @@
 // adacomp_kernels.hip -- the hot path of libadacomp as hand-written HIP for gfx950 (CDNA4,
 // wave64).  Everything here is bound by HBM traffic, not arithmetic: there is no dense
-// contraction, hence no MFMA.  All floating-point work is single additions / subtractions in
-// float32 (no multiplies, nothing to contract) plus one float64 sum and divide per layer.
+// contraction, hence no MFMA.  The floating-point work of the default method is single additions
+// and subtractions in float32 (no multiplies, nothing to contract) plus one float64 sum and divide
+// per layer; the soft-threshold factor of the variant entry point adds one multiply per element,
+// the fused optimizer step a handful of separate float32 operations per element.
 //
 // adacomp_compress runs three launches:
 //   k_fused  (streaming, dominant)  one pass over dW and the residue: G = R + dW, H = G + dW, the
@@ -12,11 +14,11 @@
 //            the packet, g_max and its per-tile float64 sum go to scratch.
 //   k_scan   one workgroup per layer: the layer scale = average of the g_max vector (section
 //            "Pseudo code") and the exclusive scan of per-tile word counts.
-//   k_place  16 lanes per tile: moves the staged entries to their final place in the packet as
-//            (index-in-bin, ternary code) words and applies the only step that needs the
+//   k_place  16 or 64 lanes per tile: moves the staged entries to their final place in the packet
+//            as (index-in-bin, ternary code) words and applies the only step that needs the
 //            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
-//            about 1-10 % of the elements); one extra workgroup writes header and records.
-// adacomp_unpack_accumulate is one launch, k_unpack: a workgroup owns a tile of the dense output
+//            about 0.3-10 % of the elements); one extra workgroup writes header and records.
+// adacomp_unpack_accumulate is one launch per word width, k_unpack: a workgroup owns a tile of the dense output
 // in LDS, a lane group owns each bin and adds the learners' +-scale in learner order, then the
 // tile is written out once with coalesced float4 stores; neighbouring tiles share a workgroup
 // and the per-bin bookkeeping.
@@ -44,7 +46,7 @@ __device__ __forceinline__ uint32_t bin_of(uint32_t e, uint32_t L_T, uint32_t ma
 // Inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS traffic): four
 // shift-and-add steps inside each row of 16 lanes, then the row totals are carried over with the
 // two row broadcasts (lane 15 of rows 0 and 2 into rows 1 and 3, lane 31 into rows 2 and 3).
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t /*lane*/)
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
 {
     v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x111, 0xF, 0xF, false));  // row_shr:1
     v += uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x112, 0xF, 0xF, false));  // row_shr:2
@@ -59,16 +61,6 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
 #pragma unroll
     for (uint32_t d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
-}
-
-__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
-{
-#pragma unroll
-    for (uint32_t d = 32; d > 0; d >>= 1) {
-        uint32_t lo = __shfl_xor(uint32_t(v), d, 64), hi = __shfl_xor(uint32_t(v >> 32), d, 64);
-        v += (uint64_t(hi) << 32) | lo;
-    }
     return v;
 }
 
@@ -234,7 +226,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     __syncthreads();
 
     // element order inside the tile is (j, wave, lane, c): exclusive prefix over the 4 J rows
-    const uint32_t row_incl = wave_incl_scan(lane < uint32_t(4 * J) ? s_wtot[lane] : 0u, lane);
+    const uint32_t row_incl = wave_incl_scan(lane < uint32_t(4 * J) ? s_wtot[lane] : 0u);
     const uint32_t tile_total = __shfl(row_incl, 4 * J - 1, 64);
 
     // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
@@ -342,7 +334,7 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
         for (uint32_t i = lo; i < hi; ++i) { const TileOut o = tile_out[ts + i]; csum += o.count; dsum += o.gmax_sum; }
     }
 
-    const uint32_t incl = wave_incl_scan(csum, lane);
+    const uint32_t incl = wave_incl_scan(csum);
     dsum = wave_sum_f64(dsum);
     if (lane == 63) s_wsum[wave] = incl;
     if (lane == 0) s_dsum[wave] = dsum;
@@ -368,9 +360,11 @@ __global__ __launch_bounds__(kScanWG) void k_scan(const CompressArgs a)
 
 // ==============================================================================================
 // k_place: staged entries -> final words; residue <- G - Gq at the sent elements; chunk offsets;
-// header, records and padding (last workgroup).  A tile sends a few dozen words at most in
-// steady state, so 16 lanes serve a tile and a workgroup serves 16 tiles; the whole grid is
-// resident at once and the kernel costs about three dependent memory round trips.
+// header, records and padding (last workgroup).  With long bins a tile sends a few dozen words at
+// most in steady state, so 16 lanes serve a tile and a workgroup serves 16 tiles; the whole grid
+// is resident at once and the kernel costs about three dependent memory round trips.  Its pace is
+// set by the scattered read-modify-writes of the residue: a bare kernel that does nothing else
+// needs as long for the same number of words.
 // ==============================================================================================
 __device__ __forceinline__ uint64_t pad16_dev(uint64_t x) { return (x + 15u) & ~uint64_t(15); }
 
@@ -411,7 +405,7 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
                 scale = layer_scale[l];
                 bytes = uint32_t(pad16_dev(uint64_t(nsel) * ld.word_bytes));
             }
-            const uint32_t incl = wave_incl_scan(bytes, lane);
+            const uint32_t incl = wave_incl_scan(bytes);
             uint32_t nsum = wave_sum(nsel);
             __syncthreads();  // previous round's readers of s_wtot are done
             if (lane == 63) s_wtot[wave] = incl;
@@ -594,7 +588,7 @@ __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDe
     for (uint32_t q = 0; q < kPerWave; ++q) {
         const uint32_t kk = wave + 4u * q;  // < kLearnerGroup; learners past nk get empty entries
         const uint32_t cq = ok[q] ? c[q] : 0u;   // a packet that does not match contributes nothing
-        const uint32_t incl = wave_incl_scan(cq, lane);
+        const uint32_t incl = wave_incl_scan(cq);
         // A bin whose words would lie past the packet's total_bytes (counts or offsets that do not
         // belong together) contributes nothing: no word is read from outside the packet.
         const uint64_t first = uint64_t(wbase[q]) + coff[q] + (incl - cq);
