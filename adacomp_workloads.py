@@ -45,9 +45,8 @@ class Workload:
 
     @property
     def n_total(self) -> int:
-        """Length of the flat buffer (last layer end; layer starts are multiples of 4)."""
-        last = self.layers[-1]
-        return last.elem_offset + last.n_elems
+        """Length of the flat buffer (end of the layer that lies last; layer starts are multiples of 4)."""
+        return max(l.elem_offset + l.n_elems for l in self.layers)
 
     @property
     def n_params(self) -> int:
@@ -110,6 +109,14 @@ def workload(index: int) -> Workload:
 def custom(name, layers, n_learners=1, n_steps=1, dist="normal") -> Workload:
     """A workload over an arbitrary [(name, n_elems, L_T)] list (edge-case tests)."""
     return Workload(0, name, _place(layers), n_learners, n_steps, dist)
+
+
+def custom_placed(name, layers, n_learners=1, n_steps=1, dist="normal") -> Workload:
+    """Like custom, with the element offset of every layer given: [(name, n_elems, L_T, elem_offset)],
+    in any order, with any gaps (offsets must be multiples of 4 and the layers must not overlap)."""
+    placed = tuple(Layer(nm, int(n), int(lt), int(off)) for nm, n, lt, off in layers)
+    assert all(l.elem_offset % 4 == 0 for l in placed)
+    return Workload(0, name, placed, n_learners, n_steps, dist)
 
 
 def _rng(seed, wl_index, learner, step, layer, block, salt=0):

@@ -148,6 +148,16 @@ def test_edge_tables(H, oracle_lib, name):
     H.run_parity(oracle_lib, wl, 3, 4, seed=7, label=name)
 
 
+def test_layers_in_any_order_with_gaps(H, oracle_lib):
+    """The layer table need not follow the buffer: layers listed out of address order, with large
+    holes between them and in front of the first; nothing outside the layers is touched."""
+    wl = W.custom_placed("scattered", [("c", 500 * 70 + 13, 500, 400000), ("a", 50 * 130 + 7, 50, 1024),
+                                       ("d", 9000, 4500, 120000), ("b", 64 * 66 + 1, 64, 64000),
+                                       ("e", 777, 9, 300000)], dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 3, seed=21, label="scattered layers")
+    H.run_parity(oracle_lib, wl, 3, 2, seed=22, label="scattered layers, batched", batch=True)
+
+
 # ------------------------------------------------------------------------------------------------
 # batched compress: several learners per launch
 # ------------------------------------------------------------------------------------------------
