@@ -275,7 +275,7 @@ def test_variant_default_equals_compress(H):
 # ------------------------------------------------------------------------------------------------
 # unpack + average + optimizer step in one pass
 # ------------------------------------------------------------------------------------------------
-def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0, threads=1):
+def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0, threads=1, grads_fn=None):
     import gpu_harness as G
     import paper_1712_02679_amd as A
     table, n = wl.table(), wl.n_total
@@ -291,7 +291,7 @@ def _update_case(oracle_lib, wl, n_learners, n_steps, kind, with_dense, seed=0, 
     try:
         for t in range(n_steps):
             G.say(f"{wl.name} update kind {kind} step {t}")
-            grads = [W.gradient(wl, k, t, seed=seed, threads=threads) for k in range(n_learners)]
+            grads = [grads_fn(k, t) if grads_fn else W.gradient(wl, k, t, seed=seed, threads=threads) for k in range(n_learners)]
             gpu.compress_batch(grads)
             if threads > 1:  # learners are independent: one oracle call per host thread
                 from concurrent.futures import ThreadPoolExecutor
@@ -418,6 +418,40 @@ def test_ties_and_zeros(H, oracle_lib):
             g = -grads(k, 1) - grads(k, 0) + f32(0.0)  # pushes many G to exact zero
         return g.astype(f32)
     H.run_parity(oracle_lib, wl, 2, 4, grads=grads, label="ties")
+
+
+def _subnormal_case():
+    """Layers whose values are all subnormal, a layer that mixes subnormal and ordinary values, and
+    a layer of very large ones."""
+    wl = W.custom("subnormal", [("a", 50 * 90 + 7, 50), ("b", 500 * 30 + 11, 500), ("c", 64 * 40, 64), ("d", 500 * 20, 500)])
+    n = wl.n_total
+    lay = wl.layers
+    tiny = float(np.finfo(f32).tiny)
+
+    def grads(k, t):
+        g = _rand(1000 * k + t, n)
+        out = np.zeros(n, f32)
+        a, b, c, d = (slice(l.elem_offset, l.elem_offset + l.n_elems) for l in lay)
+        out[a] = (g[a].astype(np.float64) * tiny * 2.0 ** -8).astype(f32)    # all subnormal
+        out[b] = (g[b].astype(np.float64) * tiny * 2.0 ** -3).astype(f32)    # subnormal, a few reach the normal range
+        mixed = g[c].copy()
+        mixed[::3] = (mixed[::3].astype(np.float64) * tiny * 0.01).astype(f32)
+        out[c] = mixed
+        out[d] = g[d] * f32(1e30)
+        return out
+    g0 = grads(0, 0)
+    assert np.count_nonzero((np.abs(g0) < tiny) & (g0 != 0)) > 10000    # the inputs really are subnormal
+    return wl, grads
+
+
+def test_subnormal_and_large_magnitudes(H, oracle_lib):
+    """Nothing on the path flushes subnormal numbers (G, g_max, the scale, the residue, the adds of the
+    unpacked sum, the optimizer steps), and magnitudes up to 1e30 pass through unharmed."""
+    wl, grads = _subnormal_case()
+    H.run_parity(oracle_lib, wl, 5, 4, grads=grads, label="subnormal")
+    H.run_parity(oracle_lib, wl, 20, 2, grads=grads, label="subnormal, batched", batch=True, check_gmax=False)
+    _update_case(oracle_lib, wl, 3, 2, 1, True, grads_fn=grads)
+    _update_case(oracle_lib, wl, 3, 2, 2, False, grads_fn=grads)
 
 
 def test_all_zero_and_all_selected(H, oracle_lib):
