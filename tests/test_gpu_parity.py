@@ -469,6 +469,26 @@ def test_all_zero_and_all_selected(H, oracle_lib):
     assert stats[1][3] == A.adacomp_packet_bound(wl.table())
 
 
+@pytest.mark.parametrize("batch", [False, True])
+def test_all_selected_every_bin_length(H, oracle_lib, batch):
+    """Every element sent, for every kind of tile and word: bins of 1, 7, 64 (8-bit words, up to 64
+    words per bin), 65, 500, 4096 (a tile per bin), 4097 and 16384 (bins cut into slices on unpack,
+    thousands of words per bin), with three learners whose signs differ, so that the unpacked sum
+    meets every address three times."""
+    import paper_1712_02679_amd as A
+    wl = W.custom("all_sent", [("a", 1000, 1), ("b", 7 * 300 + 3, 7), ("c", 64 * 70, 64), ("d", 65 * 70 + 1, 65),
+                               ("e", 500 * 20 + 250, 500), ("f", 4096 * 3, 4096), ("g", 4097 * 2 + 5, 4097),
+                               ("h", 16384 * 2 + 100, 16384)])
+    n = wl.n_total
+
+    def grads(k, t):
+        sign = np.where(np.random.default_rng(10 * k + t).random(n) < 0.5, -1, 1).astype(f32)
+        return sign * f32(0.25)
+    stats = H.run_parity(oracle_lib, wl, 3, 2, grads=grads, label="all sent", batch=batch, check_gmax=False)
+    assert all(st[2] == wl.n_params for st in stats)                       # every element, every learner and step
+    assert stats[0][3] == A.adacomp_packet_bound(wl.table())
+
+
 def test_truncated_packet(H, oracle_lib):
     """Capacity below the need: status = truncated, total_bytes = the need, the words that fit are
     the oracle's, nothing is written past the capacity, residue updated as if all had been sent."""
