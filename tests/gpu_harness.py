@@ -122,9 +122,12 @@ def compare_residue(got, want, mask, scale_hint, tag):
 
 
 def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, grads=None,
-               check_gmax=True, unpack_every_step=True, threads=8, label=None, batch=False, rule=0, soft_factor=2.0):
+               check_gmax=True, unpack_every_step=True, threads=8, label=None, batch=False, rule=0, soft_factor=2.0,
+               oracle_threads=1):
     """Free-running (default) or step-locked comparison of GPU and oracle over several steps.
-    grads: optional callable (learner, step) -> numpy float32 array overriding the generator."""
+    grads: optional callable (learner, step) -> numpy float32 array overriding the generator.
+    oracle_threads > 1 (batched runs without the g_max check): the oracle's calls of one step, one per
+    learner, run on that many host threads (the learners are independent)."""
     label = label or wl.name
     assert batch or (rule == 0 and soft_factor == 2.0), "variants go through the batched entry point"
     table, n_total = wl.table(), wl.n_total
@@ -143,6 +146,12 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
                     for k in range(n_learners):
                         gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
                 batch_bufs = gpu.compress_batch(all_g, rule, soft_factor)
+                wants = None
+                if oracle_threads > 1 and not check_gmax:
+                    from concurrent.futures import ThreadPoolExecutor
+                    with ThreadPoolExecutor(min(oracle_threads, n_learners)) as pool:
+                        wants = list(pool.map(lambda k: oracle_lib.compress(table, all_g[k], R_cpu[k], rule=rule,
+                                                                            soft_factor=soft_factor), range(n_learners)))
             for k in range(n_learners):
                 tag = f"{label} step {t} learner {k}"
                 say(tag)
@@ -150,7 +159,10 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
                 if step_locked and not batch:
                     gpu.residue[k].copy_(torch.from_numpy(R_cpu[k]))
                 R_before = R_cpu[k].copy() if check_gmax else None
-                want = oracle_lib.compress(table, g, R_cpu[k], rule=rule, soft_factor=soft_factor)
+                if batch and wants is not None:
+                    want = wants[k]
+                else:
+                    want = oracle_lib.compress(table, g, R_cpu[k], rule=rule, soft_factor=soft_factor)
                 got_buf = batch_bufs[k] if batch else gpu.compress(k, g)
                 if check_gmax:
                     G = R_before + g

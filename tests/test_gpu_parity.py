@@ -171,6 +171,12 @@ def test_batch_workload4_eight_learners(H, oracle_lib):
     H.run_parity(oracle_lib, wl, wl.n_learners, 3, batch=True, check_gmax=False)
 
 
+def test_batch_workload3_all_learners_all_steps(H, oracle_lib):
+    """ResNet-50 table as configured: 8 learners, 10 free-running steps, one batched call per step."""
+    wl = W.workload(3)
+    H.run_parity(oracle_lib, wl, wl.n_learners, wl.n_steps, batch=True, check_gmax=False, threads=16)
+
+
 @pytest.mark.parametrize("name", ["mixed_with_gaps", "LT16384_and_odd_16383", "tiny_layers", "LT64_LT65_word_width"])
 def test_batch_edge_tables(H, oracle_lib, name):
     wl = W.custom(name, EDGE_TABLES[name], dist="normal_outliers")
@@ -180,6 +186,14 @@ def test_batch_edge_tables(H, oracle_lib, name):
 def test_batch_more_learners_than_one_launch_holds(H, oracle_lib):
     wl = W.custom("batch40", [("a", 50 * 40 + 7, 50), ("b", 500 * 12 + 11, 500)])
     H.run_parity(oracle_lib, wl, 40, 2, seed=3, batch=True, check_gmax=False)
+
+
+def test_batch_workload5_sixteen_learners_free_running(H, oracle_lib):
+    """The configuration bench.py times, free-running: 16 learners of the 125 M-element table, three
+    steps of adacomp_compress_batch and a 16-packet unpack after each, every packet, residue and sum
+    against the oracle."""
+    wl = W.workload(5)
+    H.run_parity(oracle_lib, wl, 16, 3, batch=True, check_gmax=False, threads=16, oracle_threads=16)
 
 
 def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
