@@ -190,6 +190,30 @@ def pin_zero_residue_threshold_is_half_the_maximum(o):
     assert 40 < r["n_selected"] / (n / T) < 70
 
 
+def pin_expected_selection_count_of_a_gaussian_bin(o):
+    """First mini-batch with independent Gaussian dW: an element is sent iff 2|x| >= max|x| of its bin
+    (factor 2 of the soft threshold), so the expected number sent per bin of T elements is
+    T * integral of f(a) F(2a)^(T-1) da, with f and F the density and distribution of |x|.
+    The integral gives about 55 for T = 500 and 11 for T = 50, the self-adjusting rate the paper
+    describes (more is sent where the distribution is flat); the oracle must meet it within the
+    sampling error."""
+    from scipy.special import erf
+    a = np.linspace(0.0, 12.0, 240001)
+    f = np.sqrt(2.0 / np.pi) * np.exp(-0.5 * a * a)
+    values = {}
+    for T, n_bins, seed in ((500, 4000, 61), (50, 40000, 62)):
+        F2 = erf(2.0 * a / np.sqrt(2.0))
+        y = f * F2 ** (T - 1)
+        expected = T * float(np.sum((y[1:] + y[:-1]) * 0.5 * (a[1] - a[0])))
+        n = T * n_bins
+        r = o.pack_layer(np.zeros(n, f32), _rand(seed, n, 3e-3), T)
+        got = r["n_selected"] / n_bins
+        assert abs(got - expected) < 0.02 * expected, (T, got, expected)
+        values[T] = expected
+    # what the integral comes to, so that a slip in it shows too
+    assert abs(values[500] - 55.12) < 0.02 and abs(values[50] - 11.05) < 0.01
+
+
 def pin_comparison_is_greater_or_equal(o):
     """The printed compare is >=: an element whose |H| equals g_max is sent."""
     R = np.array([2.0, 1.0, 0.5, 0.0], f32)
