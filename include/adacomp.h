@@ -178,8 +178,10 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
  *            (magic, version, status, n_layers) contributes nothing.  The counts and offsets
  *            inside a packet are otherwise taken as they are; the only check is that no word is
  *            read at or beyond the header's total_bytes (a bin whose words would lie there
- *            contributes nothing), so the buffer must hold total_bytes bytes.  Whatever a
- *            packet holds, nothing outside dense_out is written.
+ *            contributes nothing), so the buffer must hold total_bytes bytes: a caller that
+ *            received the packet from elsewhere compares the header's total_bytes with the
+ *            number of bytes it received before it calls.  Whatever a packet holds, nothing
+ *            outside dense_out is written.
  * dense_out  every element of every layer is overwritten with the float32 sum, taken in learner
  *            order 0..n-1, of the decoded values (+-scale of that learner's layer where it sent
  *            the element, 0 elsewhere); 16-byte aligned.  n_learners == 0 writes zeros.
