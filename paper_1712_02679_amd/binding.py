@@ -7,6 +7,7 @@ fallback: if the library has not been built, loading raises.
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 
 import numpy as np
@@ -97,12 +98,18 @@ def _check(rc):
         raise AdacompError(rc, lib().adacomp_strerror(rc).decode())
 
 
-def layer_array(layers):
-    """[(elem_offset, n_elems, L_T)] -> ctypes array of adacomp_layer_t."""
-    arr = (Layer * max(1, len(layers)))()
-    for i, (off, n, lt) in enumerate(layers):
+@functools.lru_cache(maxsize=32)
+def _layer_array(key):
+    arr = (Layer * max(1, len(key)))()
+    for i, (off, n, lt) in enumerate(key):
         arr[i].elem_offset, arr[i].n_elems, arr[i].L_T, arr[i].reserved = int(off), int(n), int(lt), 0
     return arr
+
+
+def layer_array(layers):
+    """[(elem_offset, n_elems, L_T)] -> ctypes array of adacomp_layer_t (kept for tables seen before:
+    the library only reads it)."""
+    return _layer_array(tuple(map(tuple, layers)))
 
 
 def _stream():
