@@ -57,6 +57,13 @@ def test_workload4_char_lstm_long_run_one_learner(H, oracle_lib):
     H.run_parity(oracle_lib, wl, 1, wl.n_steps, check_gmax=False, unpack_every_step=False)  # all 50 steps
 
 
+def test_workload2_long_run(H, oracle_lib):
+    """Five times the configured number of steps, free-running: residues, packets and sums stay
+    bit-equal to the oracle's (a single differing bit would feed back through the residue)."""
+    wl = W.workload(2)
+    H.run_parity(oracle_lib, wl, wl.n_learners, 100, batch=True, check_gmax=False)
+
+
 def test_workload3_resnet50_full_size(H, oracle_lib):
     wl = W.workload(3)
     H.run_parity(oracle_lib, wl, 2, 3, check_gmax=True)                # full layer table, 2 learners x 3 steps
