@@ -1,13 +1,14 @@
 """Shared driver of the GPU parity tests: runs the same seeded inputs through libadacomp (via the
 C ABI binding) and through the CPU oracle, and compares element by element.
 
-Bars (from the benchmark spec of this build): packets bit-identical in indices, signs, counts and
+Bars: packets bit-identical in indices, signs, counts and
 layout; float32 scale within 1e-6 relative; residue within 1e-6 * max(|G|, scale) absolute.
 Because every float32 step is a single correctly rounded addition and the float64 sum of g_max
 is exact for these inputs, bit equality is expected throughout and is what the comparisons
 assert first; the tolerance form is the fallback that tells a genuine mismatch from a last-bit
 difference in the scale.
 """
+import os
 import sys
 
 import numpy as np
@@ -21,9 +22,29 @@ DEV = "cuda:0"
 POISON = 0xCD
 
 
+_PROGRESS = None
+
+
 def say(msg):
+    """Names the case about to run: on stdout (pytest shows it with -s or on failure) and, flushed, in
+    a progress log that a test runner which captures stdout does not hide (in the directory
+    ADACOMP_TEST_LOG_DIR names, else in the run-output folder of the repository if there is one,
+    else in the temporary directory)."""
+    global _PROGRESS
     print(f"[parity] {msg}", flush=True)
-    sys.stdout.flush()
+    try:
+        if _PROGRESS is None:
+            import tempfile
+            root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+            d = os.environ.get("ADACOMP_TEST_LOG_DIR") or os.path.join(root, "gpurun_out")
+            if not os.path.isdir(d):
+                d = tempfile.gettempdir()
+            _PROGRESS = open(os.path.join(d, "parity_progress.log"), "a", buffering=1)
+        if _PROGRESS:
+            _PROGRESS.write(msg + "\n")
+            _PROGRESS.flush()
+    except OSError:
+        _PROGRESS = False
 
 
 class GpuSide:
