@@ -165,6 +165,40 @@ def test_layers_in_any_order_with_gaps(H, oracle_lib):
     H.run_parity(oracle_lib, wl, 3, 2, seed=22, label="scattered layers, batched", batch=True)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_layer_tables(H, oracle_lib, seed):
+    """Forty seeded random layer tables each (1-8 layers, bin lengths from 1 to 16384 with the
+    awkward ones in between, layers from one element to 600 k, 1-33 learners, single or batched
+    calls, unpack with and without runs of tiles), two free-running steps per table."""
+    import paper_1712_02679_amd as A
+    rng = np.random.default_rng(seed)
+    lts = [1, 2, 3, 5, 7, 16, 49, 50, 63, 64, 65, 100, 255, 256, 257, 499, 500, 1000, 2048, 4095, 4096, 4097,
+           5000, 8191, 8192, 12000, 16383, 16384]
+    try:
+        for case in range(40):
+            layers = []
+            for i in range(int(rng.integers(1, 9))):
+                T = int(rng.choice(lts))
+                kind = int(rng.integers(0, 4))
+                if kind == 0:
+                    n = int(rng.integers(1, 3 * T + 2))
+                elif kind == 1:
+                    n = int(T * rng.integers(1, 200) + rng.integers(0, T))
+                elif kind == 2:
+                    n = int(rng.integers(1, 300000))
+                else:
+                    n = int(T * 64 * rng.integers(1, 6) + rng.integers(0, 64 * T))
+                layers.append((f"l{i}", max(1, min(n, 600000)), T))
+            wl = W.custom(f"random{seed}_{case}", layers, dist=str(rng.choice(["normal", "normal_outliers", "laplace"])))
+            n_learners = int(rng.choice([1, 2, 3, 5, 17, 33]))
+            batch = bool(rng.integers(0, 2))
+            A.adacomp_tuning_unpack_min_groups(1 if rng.integers(0, 2) else 0)
+            H.run_parity(oracle_lib, wl, n_learners, 2, seed=int(rng.integers(0, 1000)), batch=batch, check_gmax=False,
+                         label=f"random table {seed}/{case} {layers}")
+    finally:
+        A.adacomp_tuning_unpack_min_groups(0)
+
+
 # ------------------------------------------------------------------------------------------------
 # batched compress: several learners per launch
 # ------------------------------------------------------------------------------------------------
