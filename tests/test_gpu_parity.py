@@ -726,6 +726,19 @@ def test_checkpoint_resume(H, oracle_lib):
         b.close()
 
 
+def test_caller_written_in_c(H):
+    """The C ABI from a caller that is not Python: tests/c_driver/abi_roundtrip (C++ and the HIP
+    runtime only, built beforehand by the build entry point) runs batched and single compress
+    calls, unpack and the fused SGD step on a four-layer table and compares every byte with the
+    oracle linked into it."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_driver", "abi_roundtrip")
+    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "c caller ok" in res.stdout
+
+
 def test_copy_kernel(H):
     import paper_1712_02679_amd as A
     for n in (1, 5, 1024, 1 << 20, (1 << 22) + 3):
