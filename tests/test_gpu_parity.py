@@ -707,6 +707,37 @@ def test_hip_graph_capture_and_replay(H, oracle_lib):
         other.close()
 
 
+def test_two_streams_two_workspaces(H, oracle_lib):
+    """Calls on different streams with different workspaces do not interact: two learners are
+    compressed concurrently, each on a stream of its own, for several steps with no synchronisation
+    in between, and each gives exactly what the oracle gives."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(4)
+    table, n = wl.table(), wl.n_total
+    sides = [G.GpuSide(table, n, 1), G.GpuSide(table, n, 1)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    steps = 4
+    try:
+        grads = [[torch.from_numpy(W.gradient(wl, k, t)).to(G.DEV) for t in range(steps)] for k in range(2)]
+        packets = [[torch.full((sides[k].capacity,), G.POISON, dtype=torch.uint8, device=G.DEV) for _ in range(steps)] for k in range(2)]
+        torch.cuda.synchronize()
+        for t in range(steps):
+            for k in range(2):
+                with torch.cuda.stream(streams[k]):
+                    A.adacomp_compress(table, grads[k][t], sides[k].residue[0], packets[k][t], sides[k].ws)
+        torch.cuda.synchronize()
+        for k in range(2):
+            R = np.zeros(n, f32)
+            for t in range(steps):
+                want = oracle_lib.compress(table, grads[k][t].cpu().numpy(), R)
+                G.compare_packet(packets[k][t].cpu().numpy(), want, sides[k].capacity, f"stream {k} step {t}")
+            assert np.array_equal(sides[k].residue[0].cpu().numpy().view(np.uint32), R.view(np.uint32))
+    finally:
+        for s_ in sides:
+            s_.close()
+
+
 def test_checkpoint_resume(H, oracle_lib):
     """The residue is the only learner state: copying it out and back resumes identically."""
     import gpu_harness as G
