@@ -61,6 +61,8 @@ extern "C" {
 #define ADACOMP_ENOSPC (-4)     /* packet_capacity below the fixed part of the packet                    */
 #define ADACOMP_EHIP (-5)       /* a HIP call failed (no device, launch failure)                         */
 #define ADACOMP_EWORKSPACE (-6) /* workspace too small, or not initialised for this layer table          */
+#define ADACOMP_EPENDING (-7)   /* residue corrections of a lazy call wait in this workspace and the call
+                                   is not the lazy call that goes on with the same residue buffers      */
 
 #define ADACOMP_LT_MAX 16384u
 #define ADACOMP_CHUNK_BINS 64u
@@ -170,6 +172,31 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
                              const float *const *grads, float *const *residues, void *const *packets_out,
                              size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+
+/* pack() with the residue corrections deferred.  The last step of Algorithm 2, residue(index) <-
+ * G(index) - Gq(index) at the sent elements, is a scattered read-modify-write that costs about 6 %
+ * of the whole pack() on a large fully connected table; nothing needs its result before the same
+ * learner's next pack(), which reads the whole residue anyway.  This call sends exactly the
+ * packets adacomp_compress_batch sends, but leaves the corrections in the workspace and applies
+ * them at the start of the next lazy call, in registers.  Between the two calls residues[k] holds
+ * G (not G - Gq) at the elements that were sent.
+ *   - The next call on this workspace must be adacomp_compress_batch_lazy with the same
+ *     n_learners and the same residues[k] in the same order, or adacomp_residue_sync; every other
+ *     compress call returns ADACOMP_EPENDING and enqueues nothing.  Unpack calls are not affected.
+ *   - Before the residues are read, written, zeroed, checkpointed or freed by anyone else, and
+ *     before adacomp_workspace_init / adacomp_workspace_release of this workspace (which drop the
+ *     waiting corrections), call adacomp_residue_sync.
+ *   - The host keeps the books when a call is enqueued: use one stream per workspace.
+ * After the sync the residues are bit for bit those of the eager calls. */
+int adacomp_compress_batch_lazy(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                                const float *const *grads, float *const *residues, void *const *packets_out,
+                                size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Applies the residue corrections that the last adacomp_compress_batch_lazy on this workspace left
+ * waiting, to the residue buffers that call was given (one kernel launch on hip_stream).  Does
+ * nothing if none wait.  ADACOMP_EWORKSPACE if the workspace is not registered.  If a launch fails
+ * (ADACOMP_EHIP) the residues are unspecified and nothing is left waiting. */
+int adacomp_residue_sync(void *workspace, void *hip_stream);
 
 /* ---- unpack() of all learners, summed ("unpack()" then the sum inside "averageGradients()") -- */
 

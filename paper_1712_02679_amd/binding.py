@@ -15,12 +15,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadacomp.so")
 
-OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE, EPENDING = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = [
     "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
     "adacomp_workspace_bytes_batch", "adacomp_workspace_init", "adacomp_workspace_release",
     "adacomp_compress", "adacomp_compress_batch", "adacomp_compress_variant",
+    "adacomp_compress_batch_lazy", "adacomp_residue_sync",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
     "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_timing_enable", "adacomp_timing_read",
@@ -72,6 +73,8 @@ def lib():
         L.adacomp_workspace_bytes_batch.argtypes = [LP, u32, u32]
         L.adacomp_compress_batch.argtypes = [LP, u32, u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                              ctypes.POINTER(vp), sz, vp, sz, vp]
+        L.adacomp_compress_batch_lazy.argtypes = L.adacomp_compress_batch.argtypes
+        L.adacomp_residue_sync.argtypes = [vp, vp]
         L.adacomp_compress_variant.argtypes = [LP, u32, u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                ctypes.POINTER(vp), sz, u32, ctypes.c_float, vp, sz, vp]
         L.adacomp_workspace_init.argtypes = [LP, u32, vp, sz, vp]
@@ -164,6 +167,24 @@ def adacomp_compress_batch(layers, grads, residues, packets_out, workspace, pack
     p = (vp * n)(*[t.data_ptr() for t in packets_out])
     _check(lib().adacomp_compress_batch(layer_array(layers), len(layers), n, g, r, p, cap, _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_compress_batch_lazy(layers, grads, residues, packets_out, workspace, packet_capacity=None):
+    """adacomp_compress_batch with the residue corrections left waiting in the workspace: the next
+    call on it is this one with the same residue tensors, or adacomp_residue_sync."""
+    n = len(grads)
+    cap = min(p.numel() for p in packets_out) if packet_capacity is None else int(packet_capacity)
+    vp = ctypes.c_void_p
+    g = (vp * n)(*[t.data_ptr() for t in grads])
+    r = (vp * n)(*[t.data_ptr() for t in residues])
+    p = (vp * n)(*[t.data_ptr() for t in packets_out])
+    _check(lib().adacomp_compress_batch_lazy(layer_array(layers), len(layers), n, g, r, p, cap, _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_residue_sync(workspace):
+    """Writes the residue corrections that the last lazy call on this workspace left waiting."""
+    _check(lib().adacomp_residue_sync(_ptr(workspace), _stream()))
 
 
 RULE_ADACOMP, RULE_PRINTED_COMPARE, RULE_LOCAL_SELECTION = 0, 1, 2

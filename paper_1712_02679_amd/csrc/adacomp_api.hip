@@ -251,7 +251,10 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
 }
 
 // Workspaces that adacomp_workspace_init has filled, by address.
-struct Registered { Plan plan; size_t bytes = 0; };
+// waiting: the residue buffers, by learner slot, whose corrections of the last lazy call have not
+// been written yet (empty: none).  Kept at enqueue time, which is stream order for a workspace that
+// one stream uses at a time.
+struct Registered { Plan plan; size_t bytes = 0; std::vector<float *> waiting; };
 static std::mutex g_mu;
 static std::unordered_map<const void *, Registered> g_ws;
 
@@ -370,10 +373,10 @@ int adacomp_workspace_release(void *workspace)
     return g_ws.erase(workspace) ? ADACOMP_OK : ADACOMP_EINVAL;
 }
 
-int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
-                             const float *const *grads, float *const *residues, void *const *packets_out,
-                             size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
-                             size_t workspace_bytes, void *hip_stream)
+static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                           const float *const *grads, float *const *residues, void *const *packets_out,
+                           size_t packet_capacity, uint32_t rule, float soft_factor, bool lazy, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
 {
     if (n_learners == 0 || !grads || !residues || !packets_out) return ADACOMP_EINVAL;
     if (rule > ADACOMP_RULE_LOCAL_SELECTION || !(soft_factor >= 1.0f && soft_factor <= 16.0f)) return ADACOMP_EINVAL;
@@ -390,8 +393,24 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
     if (rc != ADACOMP_OK) return rc;
     if (packet_capacity < p.fixed_bytes) return ADACOMP_ENOSPC;
 
+    // Corrections that wait belong to the residue buffers of the call that left them: a lazy call
+    // goes on with exactly those buffers, anything else has to wait for adacomp_residue_sync.
+    bool corrections_wait = false;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        const std::vector<float *> &waiting = g_ws[workspace].waiting;
+        if (!waiting.empty()) {
+            if (!lazy || waiting.size() != n_learners) return ADACOMP_EPENDING;
+            for (uint32_t k = 0; k < n_learners; ++k)
+                if (waiting[k] != residues[k]) return ADACOMP_EPENDING;
+            corrections_wait = true;
+        }
+    }
+
     char *ws = static_cast<char *>(workspace);
     CompressArgs a;
+    a.lazy = corrections_wait ? 1u : 0u;
+    a.place_mode = lazy ? kPlaceWords : kPlaceEager;
     a.tiles = reinterpret_cast<const TileDev *>(ws + p.ws.ctiles);
     a.layers = reinterpret_cast<const LayerDev *>(ws + p.ws.layers);
     a.scratch_stride = p.ws.scratch_stride;
@@ -448,7 +467,70 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
         if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
         if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
+    if (lazy) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_ws[workspace].waiting.assign(residues, residues + n_learners);
+    }
     return ADACOMP_OK;
+}
+
+int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                             const float *const *grads, float *const *residues, void *const *packets_out,
+                             size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
+                             size_t workspace_bytes, void *hip_stream)
+{
+    return compress_common(layers, n_layers, n_learners, grads, residues, packets_out, packet_capacity, rule,
+                           soft_factor, false, workspace, workspace_bytes, hip_stream);
+}
+
+int adacomp_compress_batch_lazy(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
+                                const float *const *grads, float *const *residues, void *const *packets_out,
+                                size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return compress_common(layers, n_layers, n_learners, grads, residues, packets_out, packet_capacity,
+                           ADACOMP_RULE_ADACOMP, 2.0f, true, workspace, workspace_bytes, hip_stream);
+}
+
+int adacomp_residue_sync(void *workspace, void *hip_stream)
+{
+    if (!workspace) return ADACOMP_EINVAL;
+    Plan p;
+    std::vector<float *> waiting;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_ws.find(workspace);
+        if (it == g_ws.end()) return ADACOMP_EWORKSPACE;
+        if (it->second.waiting.empty()) return ADACOMP_OK;
+        waiting = it->second.waiting;
+        p.n_layers = it->second.plan.n_layers; p.n_ctiles = it->second.plan.n_ctiles;
+        p.has_short_bins = it->second.plan.has_short_bins; p.ws = it->second.plan.ws;
+    }
+    char *ws = static_cast<char *>(workspace);
+    CompressArgs a = {};
+    a.tiles = reinterpret_cast<const TileDev *>(ws + p.ws.ctiles);
+    a.layers = reinterpret_cast<const LayerDev *>(ws + p.ws.layers);
+    a.scratch_stride = p.ws.scratch_stride;
+    a.o_tile_out = uint32_t(p.ws.tile_out); a.o_layer_nsel = uint32_t(p.ws.layer_nsel);
+    a.o_layer_scale = uint32_t(p.ws.layer_scale); a.o_gmax = uint32_t(p.ws.gmax);
+    a.o_chunk_rel = uint32_t(p.ws.chunk_rel); a.o_stage = p.ws.stage;
+    a.n_tiles = p.n_ctiles;
+    a.n_layers = p.n_layers;
+    a.place_lanes = p.has_short_bins ? 64u : 16u;
+    a.place_mode = kPlaceResidue;
+    const uint32_t n_learners = uint32_t(waiting.size());
+    int rc = ADACOMP_OK;
+    for (uint32_t done = 0; done < n_learners; done += kMaxBatch) {
+        const uint32_t now = std::min(n_learners - done, kMaxBatch);
+        a.n_learners = now;
+        a.scratch = reinterpret_cast<uint8_t *>(ws + p.ws.scratch + p.ws.scratch_stride * done);
+        for (uint32_t k = 0; k < kMaxBatch; ++k) a.residue[k] = k < now ? waiting[done + k] : nullptr;
+        if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) break;
+    }
+    // after a failed launch some corrections may be applied and others not: nothing waits either way
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_ws.find(workspace);
+    if (it != g_ws.end()) it->second.waiting.clear();
+    return rc;
 }
 
 int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
@@ -570,6 +652,7 @@ const char *adacomp_strerror(int code)
     case ADACOMP_ENOSPC: return "packet capacity below the fixed part of the packet";
     case ADACOMP_EHIP: return "HIP runtime error (no device or failed launch)";
     case ADACOMP_EWORKSPACE: return "workspace too small or not initialised for this layer table";
+    case ADACOMP_EPENDING: return "residue corrections of a lazy call wait in this workspace: go on with the same lazy call or call adacomp_residue_sync";
     default: return "unknown adacomp error";
     }
 }

@@ -100,7 +100,10 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // ==============================================================================================
 // VARIANT = false is the method as built by default (union rule, factor 2: additions only);
 // VARIANT = true takes the selection rule and the soft-threshold factor from the arguments.
-template <int J, bool VARIANT>
+// LAZY = true: the residue corrections of the learner's previous call (residue <- G - Gq at the
+// elements it sent) are still waiting in the scratch block instead of having been written (the host
+// knows); they are applied here, to the residue values in registers, before anything else.
+template <int J, bool VARIANT, bool LAZY>
 __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
 {
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
@@ -154,6 +157,34 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
                 const bool ok = e0 + uint32_t(c) < n;
                 r[j][c] = ok ? rs[e0 + c] : 0.f;
                 w[j][c] = ok ? gr[e0 + c] : 0.f;
+            }
+        }
+    }
+    if (LAZY) {
+        // The previous call left, for this tile, its staged entries (tile-local index, sign), their
+        // number and the layer's scale.  An entry becomes a code byte in LDS at the element's place;
+        // every thread then reads the four codes of each of its slots and corrects its residues:
+        // the same single float32 subtraction or addition that the eager placement performs.
+        __shared__ __attribute__((aligned(16))) uint8_t s_fix[J * 1024];
+        const uint32_t prev_count = tile_out[tile].count;
+        const float prev_scale = reinterpret_cast<const float *>(sb + a.o_layer_scale)[td.layer()];
+        for (uint32_t i = tid; i < uint32_t(J) * 64u; i += kWG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
+        __syncthreads();
+        const uint16_t *prev_stage = stage_all + td.elem_base;
+        for (uint32_t p = tid; p < prev_count && p < n; p += kWG) {
+            const uint32_t entry = prev_stage[p];
+            if ((entry >> 2) < n) s_fix[entry >> 2] = uint8_t(entry & 3u);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+            const uint32_t codes = *reinterpret_cast<const uint32_t *>(&s_fix[e0]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t code = (codes >> (8 * c)) & 3u;
+                if (code == 1u) r[j][c] = r[j][c] - prev_scale;
+                else if (code == 3u) r[j][c] = r[j][c] + prev_scale;
             }
         }
     }
@@ -393,7 +424,11 @@ __device__ __forceinline__ uint64_t pad16_dev(uint64_t x) { return (x + 15u) & ~
 // LANES lanes serve a tile: 16 where bins are long and a tile sends a few dozen words, 64 for tables
 // with short bins, whose tiles send several hundred (5 % off the compress time of the ResNet-50
 // table, 23 % off the small CIFAR table; 64 lanes cost the 125 M-element table half a percent).
-template <uint32_t LANES>
+// MODE kPlaceEager does all of it.  kPlaceWords leaves the residue alone: the corrections wait in
+// the scratch block (staged entries, tile counts, layer scales) and the next lazy k_fused of this
+// learner applies them in registers, where they cost next to nothing; until then the residue holds
+// G at the sent elements.  kPlaceResidue applies waiting corrections and nothing else.
+template <uint32_t LANES, uint32_t MODE>
 __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 {
     constexpr uint32_t kPlaceLanes = LANES, kPlaceTiles = kWG / LANES;
@@ -408,7 +443,8 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
     uint8_t *const packet = a.packet[lr];
 
-    if (blockIdx.x == gridDim.x - 1) {
+    if (MODE == kPlaceResidue && blockIdx.x == gridDim.x - 1) return;
+    if (MODE != kPlaceResidue && blockIdx.x == gridDim.x - 1) {
         // ---- header, layer records, zero padding: 256 layers at a time, word offsets by a block
         //      scan of the padded section sizes (all below 2^32: the packet bound is) --------------
         __shared__ uint32_t s_wtot[4];
@@ -515,22 +551,25 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
         // 1 %, than this kernel gained.)
 #pragma unroll
         for (uint32_t u = 0; u < kU; ++u)
-            g[u] = (s[u] & 1u) ? rs[s[u] >> 2] : 0.f;
+            g[u] = (MODE != kPlaceWords && (s[u] & 1u)) ? rs[s[u] >> 2] : 0.f;
 #pragma unroll
         for (uint32_t u = 0; u < kU; ++u) {
             if (!(s[u] & 1u)) continue;  // codes are 1 or 3
             const uint32_t p = p0 + kPlaceLanes * u;
             const uint32_t e = s[u] >> 2, code = s[u] & 3u;
-            const uint32_t b = bin_of(e, T, M);
-            const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
-            const uint64_t at = woff + uint64_t(base + p) * wbytes;
-            if (at + wbytes <= a.capacity) {
-                if (wbytes == 1u) packet[at] = uint8_t(word);
-                else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
+            if (MODE != kPlaceResidue) {
+                const uint32_t b = bin_of(e, T, M);
+                const uint32_t word = ((e - b * T) << 2) | code;  // index inside the bin, ternary code
+                const uint64_t at = woff + uint64_t(base + p) * wbytes;
+                if (at + wbytes <= a.capacity) {
+                    if (wbytes == 1u) packet[at] = uint8_t(word);
+                    else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
+                }
             }
-            rs[e] = code == 1u ? g[u] - scale : g[u] + scale;
+            if (MODE != kPlaceWords) rs[e] = code == 1u ? g[u] - scale : g[u] + scale;
         }
     }
+    if (MODE == kPlaceResidue) return;
 
     // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
     const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
@@ -918,12 +957,15 @@ int launch_fused(const CompressArgs &a, int jcode, void *stream)
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(a.class_count * a.fused_count), wg(kWG);
     const bool variant = a.rule != ADACOMP_RULE_ADACOMP || a.soft_factor_minus_1 != 1.0f;
-    if (!variant) {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_fused<16, false>), grid, wg, 0, s, a);
+    if (a.lazy) {  // the host offers lazy residues for the default method only
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false, true>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<16, false, true>), grid, wg, 0, s, a);
+    } else if (!variant) {
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<16, false, false>), grid, wg, 0, s, a);
     } else {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, true>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_fused<16, true>), grid, wg, 0, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, true, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<16, true, false>), grid, wg, 0, s, a);
     }
     return check_launch();
 }
@@ -937,8 +979,18 @@ int launch_scan(const CompressArgs &a, void *stream)
 int launch_place(const CompressArgs &a, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (a.place_lanes == 64u) hipLaunchKernelGGL(k_place<64>, dim3((a.n_tiles + 3u) / 4u + 1u, a.n_learners), dim3(kWG), 0, s, a);
-    else hipLaunchKernelGGL(k_place<16>, dim3((a.n_tiles + 15u) / 16u + 1u, a.n_learners), dim3(kWG), 0, s, a);
+    const dim3 wg(kWG);
+    if (a.place_lanes == 64u) {
+        const dim3 grid((a.n_tiles + 3u) / 4u + 1u, a.n_learners);
+        if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<64, kPlaceWords>), grid, wg, 0, s, a);
+        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<64, kPlaceResidue>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_place<64, kPlaceEager>), grid, wg, 0, s, a);
+    } else {
+        const dim3 grid((a.n_tiles + 15u) / 16u + 1u, a.n_learners);
+        if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<16, kPlaceWords>), grid, wg, 0, s, a);
+        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<16, kPlaceResidue>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_place<16, kPlaceEager>), grid, wg, 0, s, a);
+    }
     return check_launch();
 }
 

@@ -134,6 +134,8 @@ struct CompressArgs {
     const uint32_t *class_tiles;        // tile indices by register class, or null: the launch covers tiles 0 .. class_count - 1
     uint32_t class_first, class_count;  // this launch's stretch of class_tiles
     uint32_t place_lanes;               // lanes per tile in k_place: 16 or 64
+    uint32_t place_mode;                // kPlaceEager / kPlaceWords / kPlaceResidue
+    uint32_t lazy;                      // k_fused applies the waiting residue corrections of the previous call
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2
     uint64_t o_stage;
@@ -162,6 +164,9 @@ struct UnpackArgs {
 int launch_fused(const CompressArgs &a, int jcode, void *stream);
 int launch_scan(const CompressArgs &a, void *stream);
 int launch_place(const CompressArgs &a, void *stream);
+// what a k_place launch does: everything (the default); the words, offsets and header only, leaving
+// the residue corrections waiting; or those corrections only
+constexpr uint32_t kPlaceEager = 0, kPlaceWords = 1, kPlaceResidue = 2;
 int launch_unpack(const UnpackArgs &a, int kind, void *stream);  // kind 0: 16-bit words, 1: 8-bit, 2: both
 int launch_copy(float *dst, const float *src, size_t n, void *stream);
 

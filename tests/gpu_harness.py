@@ -209,3 +209,51 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
     finally:
         gpu.close()
     return stats
+
+
+def run_lazy_parity(oracle_lib, wl, n_learners, n_steps, sync_every, seed=0, threads=8, oracle_threads=1, label=None):
+    """adacomp_compress_batch_lazy against the oracle, free-running.  Every step: every packet and
+    the 16-packet sum, and the residue as the call leaves it (G everywhere: the corrections wait).
+    After every sync_every-th step and after the last one: adacomp_residue_sync, then the residue
+    against the oracle's (0: only after the last step)."""
+    from concurrent.futures import ThreadPoolExecutor
+    label = label or ("lazy " + wl.name)
+    table, n_total = wl.table(), wl.n_total
+    mask = layer_mask(table, n_total)
+    gpu = GpuSide(table, n_total, n_learners, batch=True)
+    R_cpu = [np.zeros(n_total, np.float32) for _ in range(n_learners)]
+    try:
+        for t in range(n_steps):
+            say(f"{label} step {t} lazy batch of {n_learners}")
+            all_g = [W.gradient(wl, k, t, seed=seed, threads=threads) for k in range(n_learners)]
+            G_want = [R_cpu[k] + all_g[k] for k in range(n_learners)]   # float32: what pack() accumulates
+            g_dev = [torch.from_numpy(x).to(DEV) for x in all_g]
+            for p in gpu.packets:
+                p.fill_(POISON)
+            A.adacomp_compress_batch_lazy(table, g_dev, gpu.residue, gpu.packets, gpu.ws, packet_capacity=gpu.capacity)
+            torch.cuda.synchronize()
+            with ThreadPoolExecutor(max(1, min(oracle_threads, n_learners))) as pool:
+                wants = list(pool.map(lambda k: oracle_lib.compress(table, all_g[k], R_cpu[k]), range(n_learners)))
+            for k in range(n_learners):
+                tag = f"{label} step {t} learner {k}"
+                say(tag)
+                compare_packet(gpu.packets[k].cpu().numpy(), wants[k], gpu.capacity, tag)
+                got_r = gpu.residue[k].cpu().numpy()
+                assert np.array_equal(got_r[mask].view(np.uint32), G_want[k][mask].view(np.uint32)), \
+                    f"{tag}: before the sync the residue is G"
+            say(f"{label} step {t} unpack of {n_learners}")
+            got = gpu.unpack(list(range(n_learners)))
+            want = oracle_lib.unpack_accumulate(table, wants, n_total)
+            assert np.array_equal(got[mask].view(np.uint32), want[mask].view(np.uint32)), f"{label} step {t}: dense sum differs"
+            if (sync_every and (t + 1) % sync_every == 0) or t == n_steps - 1:
+                say(f"{label} step {t} residue sync")
+                A.adacomp_residue_sync(gpu.ws)
+                torch.cuda.synchronize()
+                for k in range(n_learners):
+                    h, layers = pf.parse(wants[k], check=False)
+                    scale_hint = max(float(l["rec"]["scale"]) for l in layers)
+                    got_r = gpu.residue[k].cpu().numpy()
+                    compare_residue(got_r, R_cpu[k], mask, scale_hint, f"{label} step {t} learner {k} after the sync")
+                    assert np.all(got_r[~mask] == 0)
+    finally:
+        gpu.close()

@@ -279,6 +279,84 @@ def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
 # ------------------------------------------------------------------------------------------------
 # selection variants: the printed compare alone, local selection, other soft-threshold factors
 # ------------------------------------------------------------------------------------------------
+# ------------------------------------------------------------------------------------------------
+# lazy residue: the corrections of a call are applied by the next call, or by adacomp_residue_sync
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("sync_every", [0, 1, 3])
+def test_lazy_workload2(H, oracle_lib, sync_every):
+    wl = W.workload(2)
+    H.run_lazy_parity(oracle_lib, wl, wl.n_learners, 7, sync_every)
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_TABLES))
+def test_lazy_edge_tables(H, oracle_lib, name):
+    wl = W.custom(name, EDGE_TABLES[name], dist="normal_outliers")
+    H.run_lazy_parity(oracle_lib, wl, 3, 5, 2, seed=17, label="lazy " + name)
+
+
+def test_lazy_more_learners_than_one_launch_holds(H, oracle_lib):
+    wl = W.custom("lazy40", [("a", 50 * 40 + 7, 50), ("b", 500 * 12 + 11, 500)])
+    H.run_lazy_parity(oracle_lib, wl, 40, 3, 0, seed=3)
+
+
+def test_lazy_workload3_and_workload5(H, oracle_lib):
+    """The two large tables (short bins with both tile classes; the table bench.py times, with one
+    streaming launch per learner), four free-running lazy steps with a sync in the middle."""
+    wl = W.workload(3)
+    H.run_lazy_parity(oracle_lib, wl, 4, 4, 2, threads=16, oracle_threads=4)
+    wl = W.workload(5)
+    H.run_lazy_parity(oracle_lib, wl, 4, 4, 2, threads=16, oracle_threads=4)
+
+
+def test_lazy_bookkeeping(H, oracle_lib):
+    """While corrections wait, every compress call but the lazy one with the same residue buffers is
+    refused and enqueues nothing; a sync with nothing waiting does nothing; after the sync the eager
+    calls go on from the same residue the eager calls alone would have reached."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.custom("lazy_books", [("a", 50 * 300 + 7, 50), ("b", 500 * 70 + 11, 500)])
+    table, n = wl.table(), wl.n_total
+    mask = G.layer_mask(table, n)
+    lazy, eager = G.GpuSide(table, n, 2, batch=True), G.GpuSide(table, n, 2, batch=True)
+    try:
+        A.adacomp_residue_sync(lazy.ws)                       # nothing waits: no-op
+        other = [torch.zeros_like(r) for r in lazy.residue]
+        for t in range(4):
+            g = [torch.from_numpy(W.gradient(wl, k, t, seed=5)).to(G.DEV) for k in range(2)]
+            A.adacomp_compress_batch_lazy(table, g, lazy.residue, lazy.packets, lazy.ws)
+            A.adacomp_compress_batch(table, g, eager.residue, eager.packets, eager.ws)
+            torch.cuda.synchronize()
+            before = [r.clone() for r in lazy.residue], [p.clone() for p in lazy.packets]
+            for call in (lambda: A.adacomp_compress_batch(table, g, lazy.residue, lazy.packets, lazy.ws),
+                         lambda: A.adacomp_compress(table, g[0], lazy.residue[0], lazy.packets[0], lazy.ws),
+                         lambda: A.adacomp_compress_variant(table, g, lazy.residue, lazy.packets, lazy.ws, rule=1),
+                         lambda: A.adacomp_compress_batch_lazy(table, g, other, lazy.packets, lazy.ws),
+                         lambda: A.adacomp_compress_batch_lazy(table, g, lazy.residue[::-1], lazy.packets, lazy.ws),
+                         lambda: A.adacomp_compress_batch_lazy(table, g[:1], lazy.residue[:1], lazy.packets[:1], lazy.ws)):
+                with pytest.raises(A.AdacompError) as e:
+                    call()
+                assert e.value.code == A.binding.EPENDING
+            torch.cuda.synchronize()
+            for k in range(2):
+                assert torch.equal(before[0][k], lazy.residue[k]) and torch.equal(before[1][k], lazy.packets[k])
+                assert torch.equal(lazy.packets[k], eager.packets[k]), f"step {t} learner {k}"
+        A.adacomp_residue_sync(lazy.ws)
+        A.adacomp_residue_sync(lazy.ws)                       # twice: the second finds nothing
+        torch.cuda.synchronize()
+        for k in range(2):
+            assert torch.equal(lazy.residue[k], eager.residue[k])
+        g = [torch.from_numpy(W.gradient(wl, k, 9, seed=5)).to(G.DEV) for k in range(2)]
+        A.adacomp_compress_batch(table, g, lazy.residue, lazy.packets, lazy.ws)   # accepted again
+        A.adacomp_compress_batch(table, g, eager.residue, eager.packets, eager.ws)
+        torch.cuda.synchronize()
+        for k in range(2):
+            assert torch.equal(lazy.residue[k], eager.residue[k]) and torch.equal(lazy.packets[k], eager.packets[k])
+        assert mask.any()
+    finally:
+        lazy.close()
+        eager.close()
+
+
 @pytest.mark.parametrize("rule,factor", [(1, 2.0), (2, 2.0), (0, 1.5), (0, 3.0), (0, 1.0), (1, 2.5), (0, 2.75)])
 def test_variants_workload2(H, oracle_lib, rule, factor):
     wl = W.workload(2)
