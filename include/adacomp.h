@@ -186,7 +186,9 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
  *   - Before the residues are read, written, zeroed, checkpointed or freed by anyone else, and
  *     before adacomp_workspace_init / adacomp_workspace_release of this workspace (which drop the
  *     waiting corrections), call adacomp_residue_sync.
- *   - The host keeps the books when a call is enqueued: use one stream per workspace.
+ *   - The host keeps the books when a call is enqueued: use one stream per workspace.  A HIP graph
+ *     holds the kernels of the call as it was captured: capture a lazy call while corrections
+ *     wait (after a first lazy call outside the capture) and replay it only in that state.
  * After the sync the residues are bit for bit those of the eager calls. */
 int adacomp_compress_batch_lazy(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
                                 const float *const *grads, float *const *residues, void *const *packets_out,

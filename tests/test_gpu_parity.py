@@ -785,6 +785,57 @@ def test_hip_graph_capture_and_replay(H, oracle_lib):
         other.close()
 
 
+def test_hip_graph_replay_of_the_lazy_call(H, oracle_lib):
+    """A graph holds the kernels of the call that was captured: a lazy call captured while
+    corrections wait (here: after a first lazy call, on zero gradients) applies the previous replay's
+    corrections at every replay.  Packets and sums against the oracle at every replay, residues after
+    the sync that follows the last one."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(2)
+    table, n, nl = wl.table(), wl.n_total, 3
+    mask = G.layer_mask(table, n)
+    gpu = G.GpuSide(table, n, nl, batch=True)
+    other = G.GpuSide(table, n, 1)
+    try:
+        static_g = [torch.zeros(n, dtype=torch.float32, device=G.DEV) for _ in range(nl)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                       # first lazy call, outside capture: nothing is sent
+            A.adacomp_compress_batch_lazy(table, static_g, gpu.residue, gpu.packets, gpu.ws)
+            A.adacomp_unpack_accumulate(table, gpu.packets, gpu.dense, gpu.ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            A.adacomp_compress_batch_lazy(table, static_g, gpu.residue, gpu.packets, gpu.ws)
+            A.adacomp_unpack_accumulate(table, gpu.packets, gpu.dense, gpu.ws)
+        R_cpu = [np.zeros(n, f32) for _ in range(nl)]
+        for t in range(5):
+            G.say(f"lazy graph replay {t}")
+            grads = [W.gradient(wl, k, t) for k in range(nl)]
+            for k in range(nl):
+                static_g[k].copy_(torch.from_numpy(grads[k]))
+            for p in gpu.packets:
+                p.fill_(G.POISON)
+            graph.replay()
+            torch.cuda.synchronize()
+            want = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(nl)]
+            for k in range(nl):
+                G.compare_packet(gpu.packets[k].cpu().numpy(), want[k], gpu.capacity, f"lazy replay {t} learner {k}")
+            dense = oracle_lib.unpack_accumulate(table, want, n)
+            assert np.array_equal(gpu.dense.cpu().numpy()[mask].view(np.uint32), dense[mask].view(np.uint32))
+            other.compress(0, grads[0])                      # eager work on other buffers between the replays
+            other.unpack([0])
+        A.adacomp_residue_sync(gpu.ws)
+        torch.cuda.synchronize()
+        for k in range(nl):
+            G.compare_residue(gpu.residue[k].cpu().numpy(), R_cpu[k], mask, 1.0, f"lazy replays, learner {k}, after the sync")
+    finally:
+        gpu.close()
+        other.close()
+
+
 def test_two_streams_two_workspaces(H, oracle_lib):
     """Calls on different streams with different workspaces do not interact: two learners are
     compressed concurrently, each on a stream of its own, for several steps with no synchronisation
