@@ -239,15 +239,19 @@ def main():
         for r in residue:
             r.zero_()
         torch.cuda.synchronize()
-        l0, l1, l2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        l1, l2 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+        lev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+        torch.cuda.synchronize()
         t1 = time.perf_counter()
-        l0.record()
-        for t in range(K):
+        for t in range(K):   # the same three event records per step as the eager loop above
+            lev[t][0].record()
             rc = L.adacomp_compress_batch_lazy(layers_c, len(table), n_learners, grad_ptrs[t % n_learners], res_ptrs,
                                                pk_ptrs, bound, ws_p, ws_n, stream)
             if rc:
                 raise RuntimeError(f"adacomp_compress_batch_lazy: {rc}")
+            lev[t][1].record()
             unpack_all()
+            lev[t][2].record()
         l1.record()
         rc = L.adacomp_residue_sync(ws_p, stream)
         if rc:
@@ -257,6 +261,8 @@ def main():
         lazy_ms = (time.perf_counter() - t1) * 1e3 / K
         lazy = {"value": round(grad_bytes_per_step / (lazy_ms * 1e-3) / 1e9, 2), "unit": "GB/s",
                 "ms_per_step": round(lazy_ms, 4), "sync_ms": round(l1.elapsed_time(l2), 4),
+                "compress_ms_per_step": round(sum(lev[t][0].elapsed_time(lev[t][1]) for t in range(K)) / K, 4),
+                "unpack_ms_per_step": round(sum(lev[t][1].elapsed_time(lev[t][2]) for t in range(K)) / K, 4),
                 "steps": K, "syncs_in_timed_region": 1, "vs_eager": round(ms_per_step / lazy_ms, 4)}
     except Exception as e:  # the main line must not depend on this leg
         L.adacomp_residue_sync(ws_p, stream)
