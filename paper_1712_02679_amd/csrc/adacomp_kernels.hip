@@ -18,6 +18,9 @@
 //            as (index-in-bin, ternary code) words and applies the only step that needs the
 //            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
 //            about 0.3-10 % of the elements); one extra workgroup writes header and records.
+// adacomp_compress_batch_lazy runs the same three, but k_place leaves that read-modify-write out
+// and the next call's k_fused applies the corrections to the residue values while it has them in
+// registers (same arithmetic, same results; adacomp_residue_sync writes them on request).
 // adacomp_unpack_accumulate is one launch per word width, k_unpack: a workgroup owns a tile of the dense output
 // in LDS, a lane group owns each bin and adds the learners' +-scale in learner order, then the
 // tile is written out once with coalesced float4 stores; neighbouring tiles share a workgroup

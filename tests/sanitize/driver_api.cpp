@@ -153,6 +153,9 @@ int main()
         if (adacomp_compress(t.data(), n_layers, g, r, pk, bound, fake + 3072, ws1, nullptr) != ADACOMP_EWORKSPACE) return 4;
         const void *pks[1] = {pk};
         if (adacomp_unpack_accumulate(t.data(), n_layers, pks, 1, r, fake + 3072, ws1, nullptr) != ADACOMP_EWORKSPACE) return 5;
+        void *pko[1] = {pk};
+        if (adacomp_compress_batch_lazy(t.data(), n_layers, 1, &g, &r, pko, bound, fake + 3072, ws1, nullptr) != ADACOMP_EWORKSPACE) return 9;
+        if (adacomp_residue_sync(fake + 3072, nullptr) != ADACOMP_EWORKSPACE || adacomp_residue_sync(nullptr, nullptr) != ADACOMP_EINVAL) return 10;
         // a broken copy of the table is refused
         std::vector<adacomp_layer_t> b = t;
         b[next() % n_layers].L_T = 16385;

@@ -89,6 +89,15 @@ def test_error_codes_without_touching_the_gpu(L):
     rc = L.adacomp_workspace_init(t, 1, p(base + 16384), 16, None)
     assert rc == binding.EWORKSPACE
     assert L.adacomp_workspace_release(p(base)) == binding.EINVAL
+    # the lazy pair: same checks as the eager call; a sync needs a registered workspace
+    gp, rp, pp = (p * 1)(base), (p * 1)(base + 4096), (p * 1)(base + 8192)
+    rc = L.adacomp_compress_batch_lazy(t, 1, 1, gp, rp, pp, 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EWORKSPACE
+    rc = L.adacomp_compress_batch_lazy(t, 1, 1, gp, gp, pp, 4096, p(base + 16384), 1 << 14, None)
+    assert rc == binding.EINVAL
+    assert L.adacomp_residue_sync(None, None) == binding.EINVAL
+    assert L.adacomp_residue_sync(p(base + 16384), None) == binding.EWORKSPACE
+    assert b"adacomp_residue_sync" in L.adacomp_strerror(binding.EPENDING)
     assert b"L_T" in L.adacomp_strerror(binding.EBADLT)
 
 
