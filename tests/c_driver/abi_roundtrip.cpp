@@ -2,7 +2,8 @@
 // memory comes from the HIP runtime; the expected results come from the CPU oracle, which is linked
 // in as the checker.  Two learners, three steps of adacomp_compress_batch with one
 // adacomp_unpack_accumulate per step, a single-learner adacomp_compress, then one
-// adacomp_unpack_update; packets, residues, the dense sum and the updated weights must equal the
+// adacomp_unpack_update, then two steps of adacomp_compress_batch_lazy and an adacomp_residue_sync;
+// packets, residues, the dense sum and the updated weights must equal the
 // oracle's byte for byte.  Built by tests/c_driver/build.py (called from the repository's build
 // entry point), run by tests/test_gpu_parity.py::test_caller_written_in_c.
 #include <hip/hip_runtime.h>
@@ -118,6 +119,36 @@ int main()
     if (std::memcmp(got.data(), w.data(), n_total * 4) != 0) { std::printf("updated weights differ\n"); return 4; }
     HIP_OK(hipMemcpy(got.data(), d_m, n_total * 4, hipMemcpyDeviceToHost));
     if (std::memcmp(got.data(), m.data(), n_total * 4) != 0) { std::printf("momentum buffer differs\n"); return 4; }
+
+    // two more mini-batches of both learners with the residue corrections deferred: packets as the
+    // oracle's at every step, an eager call refused in between, residues equal after the sync
+    for (uint32_t t = 0; t < 2; ++t) {
+        for (uint32_t k = 0; k < n_learners; ++k) {
+            for (size_t i = 0; i < n_total; ++i) grad[k][i] = draw((uint64_t(200 + t) << 40) | (uint64_t(k) << 32) | i, 0.03f);
+            HIP_OK(hipMemcpy(d_grad[k], grad[k].data(), n_total * 4, hipMemcpyHostToDevice));
+            std::memset(want_pk[k].data(), 0, bound);
+            pk_bytes[k] = adacomp_oracle_compress(otable, n_layers, grad[k].data(), res[k].data(), want_pk[k].data(), bound, 0, 2.0f);
+            if (pk_bytes[k] <= 0) return 1;
+        }
+        const float *grads[n_learners] = {d_grad[0], d_grad[1]};
+        float *residues[n_learners] = {d_res[0], d_res[1]};
+        LIB_OK(adacomp_compress_batch_lazy(table, n_layers, n_learners, grads, residues, d_pk, bound, ws, ws_bytes, stream));
+        if (adacomp_compress_batch(table, n_layers, n_learners, grads, residues, d_pk, bound, ws, ws_bytes, stream) != ADACOMP_EPENDING) {
+            std::printf("lazy step %u: an eager call was accepted while corrections wait\n", t);
+            return 4;
+        }
+        HIP_OK(hipStreamSynchronize(stream));
+        for (uint32_t k = 0; k < n_learners; ++k) {
+            HIP_OK(hipMemcpy(got_pk[k].data(), d_pk[k], size_t(pk_bytes[k]), hipMemcpyDeviceToHost));
+            if (std::memcmp(got_pk[k].data(), want_pk[k].data(), size_t(pk_bytes[k])) != 0) { std::printf("lazy step %u learner %u: packet differs\n", t, k); return 4; }
+        }
+    }
+    LIB_OK(adacomp_residue_sync(ws, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+    for (uint32_t k = 0; k < n_learners; ++k) {
+        HIP_OK(hipMemcpy(got.data(), d_res[k], n_total * 4, hipMemcpyDeviceToHost));
+        if (std::memcmp(got.data(), res[k].data(), n_total * 4) != 0) { std::printf("after the sync: residue of learner %u differs\n", k); return 4; }
+    }
 
     LIB_OK(adacomp_workspace_release(ws));
     std::printf("c caller ok: %u steps x %u learners, last packet %lld bytes of at most %zu\n", n_steps, n_learners, pk_bytes[0], bound);
