@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--learners", type=int, default=0, help="override the workload's learner count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one step captured in a HIP graph (for the small, launch-bound workloads; "
+                         "no roofline object, since events cannot be read back from a graph)")
     ap.add_argument("--batch", choices=["on", "off"], default="on",
                     help="on: one adacomp_compress_batch call per step (the library launches the streaming kernel "
                          "once per learner for large gradients and once per call for small ones; scan and placement "
@@ -103,6 +106,8 @@ def main():
     L = binding.lib()
     import ctypes
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if args.graph:
+        args.no_kernel_events = True
     ws_p, ws_n = ctypes.c_void_p(ws.data_ptr()), ws.numel()
     pk_ptrs = (ctypes.c_void_p * n_learners)(*[p.data_ptr() for p in packets])
 
@@ -111,7 +116,10 @@ def main():
     grad_ptrs = [(vp * n_learners)(*[grads[(k + t) % n_learners].data_ptr() for k in range(n_learners)])
                  for t in range(n_learners)]
 
+    cur = {"stream": stream}   # the stream the calls go to: torch's current one, or the capture stream
+
     def compress_all(t):
+        stream = cur["stream"]
         if not args.no_batch:
             rc = L.adacomp_compress_batch(layers_c, len(table), n_learners, grad_ptrs[t % n_learners], res_ptrs,
                                           pk_ptrs, bound, ws_p, ws_n, stream)
@@ -127,7 +135,7 @@ def main():
 
     def unpack_all():
         rc = L.adacomp_unpack_accumulate(layers_c, len(table), pk_ptrs, n_learners,
-                                         ctypes.c_void_p(dense.data_ptr()), ws_p, ws_n, stream)
+                                         ctypes.c_void_p(dense.data_ptr()), ws_p, ws_n, cur["stream"])
         if rc:
             raise RuntimeError(f"adacomp_unpack_accumulate: {rc}")
 
@@ -151,6 +159,17 @@ def main():
         r.zero_()
     torch.cuda.synchronize()
 
+    # ---- optional: one step (gradient set 0) captured in a HIP graph, replayed K times ----------------
+    graph = None
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cur["stream"] = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+            compress_all(0)
+            unpack_all()
+        cur["stream"] = stream
+        torch.cuda.synchronize()
+
     # ---- timed region ------------------------------------------------------------------------------
     use_events = not args.no_kernel_events
     A.adacomp_timing_enable(5 if use_events else 0)   # every 5th k_fused launch: rotates through the learners
@@ -158,6 +177,9 @@ def main():
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for t in range(K):
+        if graph is not None:
+            graph.replay()
+            continue
         ev[t][0].record()
         compress_all(t)
         ev[t][1].record()
@@ -165,11 +187,18 @@ def main():
         ev[t][2].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    if graph is not None:   # no per-call split inside a graph: record once around nothing so the sums below read 0
+        for t in range(K):
+            for e in ev[t]:
+                e.record()
+        torch.cuda.synchronize()
     fused_ms, fused_n, fused_learners = A.adacomp_timing_read() if use_events else (0.0, 0, 0)
     A.adacomp_timing_enable(0)
 
     compress_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in range(K)) / K
     unpack_ms = sum(ev[t][1].elapsed_time(ev[t][2]) for t in range(K)) / K
+    if graph is not None:
+        compress_ms = unpack_ms = float("nan")   # a replay is one submission: no split
     ms_per_step = elapsed * 1e3 / K
     log("per step compress ms: " + " ".join(f"{ev[t][0].elapsed_time(ev[t][1]):.3f}" for t in range(K)))
     log("per step unpack   ms: " + " ".join(f"{ev[t][1].elapsed_time(ev[t][2]):.3f}" for t in range(K)))
@@ -311,11 +340,13 @@ def main():
         "config": {"workload": f"{wl.name} (configuration {wl.index}): {len(table)} layers, {n_params} fp32 elements, "
                                f"L_T {sorted(set(l[2] for l in table))}, {n_learners} simulated learners, residues start at zero",
                    "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0,
-                   "compress_call": "adacomp_compress" if args.no_batch else "adacomp_compress_batch"},
+                   "compress_call": "adacomp_compress" if args.no_batch else "adacomp_compress_batch",
+                   "launch": "hip_graph_replay" if args.graph else "direct"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),
-        "compress_ms_per_step": round(compress_ms, 4), "unpack_ms_per_step": round(unpack_ms, 4),
+        "compress_ms_per_step": None if graph is not None else round(compress_ms, 4),
+        "unpack_ms_per_step": None if graph is not None else round(unpack_ms, 4),
         "unpack_update": upd,
         "lazy_residue": lazy,
         "compression": {"paper_accounting": round(ratio_paper, 2), "wire": round(ratio_wire, 2),

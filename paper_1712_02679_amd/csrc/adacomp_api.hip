@@ -74,6 +74,13 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     uint64_t words_bound = 0;
     uint64_t n_ctiles = 0, n_utiles = 0, bins_total = 0, chunks_total = 0;
 
+    // A table that makes fewer tiles of 4096 elements than there are compute units cannot fill the GPU,
+    // and the time of a launch is then the time of one tile: such tables get smaller tiles, down to
+    // 1024 elements (the 397 k-element table: 97 tiles become 265, 23 -> 19 us per compress call).
+    uint64_t elems_all = 0;
+    for (uint32_t l = 0; l < n_layers; ++l) elems_all += layers[l].n_elems;
+    const uint32_t small_cap = uint32_t(std::min<uint64_t>(4096u, std::max<uint64_t>(1024u, elems_all / kComputeUnits)));
+
     for (uint32_t l = 0; l < n_layers; ++l) {
         const uint32_t T = layers[l].L_T;
         const uint32_t n = uint32_t(layers[l].n_elems);
@@ -101,9 +108,11 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         // (measured on a plain triad), so there is no class in between.
         const int cls = T > 4096u ? 1 : 0;
         const uint32_t cap = cls ? 16384u : 4096u;
-        uint32_t bpt = cap / T;                       // >= 1
+        uint32_t bpt = (cls ? cap : small_cap) / T;
+        if (bpt == 0) bpt = 1;                        // a bin of up to cap elements always fits its class
         if (bpt > kMaxTileBins) bpt = kMaxTileBins;
         const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
+        if (bpt < a && uint64_t(a) * T <= cap) bpt = a;
         if (bpt >= a) bpt -= bpt % a;
         const uint32_t nt = (n_bins + bpt - 1) / bpt;
         ld.ctile_start = uint32_t(n_ctiles);
@@ -373,6 +382,15 @@ int adacomp_workspace_release(void *workspace)
     return g_ws.erase(workspace) ? ADACOMP_OK : ADACOMP_EINVAL;
 }
 
+// Lanes per tile in k_place: 64 for tables with short bins, whose tiles send several hundred words,
+// and for small tables, where the launch is far from filling the GPU and the words of a tile are
+// better spread over more lanes (the 397 k-element table sends 440 words per tile in its first
+// steps: 37 -> 23 us per compress call); 16 otherwise.
+static uint32_t place_lanes_for(const Plan &p)
+{
+    return (p.has_short_bins || p.n_ctiles <= 2048u) ? 64u : 16u;
+}
+
 static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
                            const float *const *grads, float *const *residues, void *const *packets_out,
                            size_t packet_capacity, uint32_t rule, float soft_factor, bool lazy, void *workspace,
@@ -421,7 +439,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.n_layers = p.n_layers;
     a.keep_gmax = g_keep_gmax ? 1u : 0u;
     a.class_tiles = (p.n_class_tiles[0] && p.n_class_tiles[1]) ? reinterpret_cast<const uint32_t *>(ws + p.ws.cclass) : nullptr;
-    a.place_lanes = p.has_short_bins ? 64u : 16u;
+    a.place_lanes = place_lanes_for(p);
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;
@@ -515,7 +533,7 @@ int adacomp_residue_sync(void *workspace, void *hip_stream)
     a.o_chunk_rel = uint32_t(p.ws.chunk_rel); a.o_stage = p.ws.stage;
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
-    a.place_lanes = p.has_short_bins ? 64u : 16u;
+    a.place_lanes = place_lanes_for(p);
     a.place_mode = kPlaceResidue;
     const uint32_t n_learners = uint32_t(waiting.size());
     int rc = ADACOMP_OK;

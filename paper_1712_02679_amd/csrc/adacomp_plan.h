@@ -12,6 +12,7 @@ namespace adacomp {
 
 constexpr uint32_t kWG = 256;            // threads per workgroup in every kernel (4 wave64)
 constexpr uint32_t kMaxTileBins = 1024;  // bins per compress tile (LDS arrays)
+constexpr uint32_t kComputeUnits = 256;  // of an MI355X: what a small table's tiles are sized against
 // elements per unpack tile: 16 KB of LDS accumulators (8192 was 10 % faster for the plain sum but
 // 12 % slower with the optimizer epilogue)
 constexpr uint32_t kUnpackTileElems = 4096;
