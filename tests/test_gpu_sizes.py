@@ -1,0 +1,78 @@
+"""GPU parity at the largest sizes the interface accepts.  These cases move tens of gigabytes and
+keep the single-threaded CPU oracle busy for a minute or two each, so they sit in a file of their
+own that runs after the other GPU tests."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import adacomp_workloads as W  # noqa: E402
+
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+@pytest.mark.parametrize("L_T", [64, 16384])
+def test_largest_layer_the_abi_accepts(H, oracle_lib, L_T):
+    """One layer as long as the interface allows: 2^31 - 1 elements with 8-bit words, and with 16-bit
+    words the longest layer whose packet bound stays below 4 GiB (found by bisection on
+    adacomp_packet_bound, so the host's limit is part of the test).  One pack() from a non-zero
+    residue and one unpack(), every byte and element against the oracle.  The 8-bit case takes
+    seeded gradients with outliers (element offsets beyond 2^31 bytes, half a million tiles); the
+    16-bit case sends every element (equal magnitudes, random signs), so that the packet is exactly
+    as long as the bound and the last words sit just below 2^32."""
+    import gpu_harness as G
+    import packet_format as pf
+    import paper_1712_02679_amd as A
+    lo, hi = 1, 2 ** 31 - 1
+    while lo < hi:                                   # largest n with a packet bound the library accepts
+        mid = (lo + hi + 1) // 2
+        if A.adacomp_packet_bound([(0, mid, L_T)]) > 0:
+            lo = mid
+        else:
+            hi = mid - 1
+    n = lo
+    assert (n == 2 ** 31 - 1) if L_T == 64 else (2 ** 31 - 2 ** 20 < n < 2 ** 31 - 1)
+    assert L_T == 64 or A.adacomp_packet_bound([(0, n + 1, L_T)]) == 0
+    wl = W.custom(f"longest_LT{L_T}", [("a", n, L_T)], dist="normal_outliers")
+    table = wl.table()
+    G.say(f"longest layer L_T {L_T}: {n} elements, generating")
+    if L_T == 64:
+        g = W.gradient(wl, 0, 0, seed=31, threads=16)
+        R = W.gradient(wl, 1, 7, seed=31, threads=16)
+        R *= f32(0.5)
+    else:
+        g = np.full(n, 0.25, f32)
+        g[np.random.default_rng(31).integers(0, 2, n, dtype=np.int8) == 1] = f32(-0.25)
+        R = g.copy()                                 # G = 2 dW: every |G| is the bin maximum
+    gpu = G.GpuSide(table, n, 1)
+    try:
+        gpu.residue[0].copy_(torch.from_numpy(R))
+        G.say(f"longest layer L_T {L_T}: compress on the GPU")
+        got = gpu.compress(0, g)
+        G.say(f"longest layer L_T {L_T}: oracle")
+        want = oracle_lib.compress(table, g, R)
+        del g
+        assert L_T == 64 or (want.size == A.adacomp_packet_bound(table) and not R.any())
+        assert int(pf.header(got)["total_bytes"]) == want.size
+        assert np.array_equal(got[:want.size], want), "packet differs from the oracle"
+        assert np.all(got[want.size:] == G.POISON)
+        del got
+        got_r = gpu.residue[0].cpu().numpy()
+        assert np.array_equal(got_r.view(np.uint32), R.view(np.uint32)), "residue differs from the oracle"
+        del got_r, R
+        G.say(f"longest layer L_T {L_T}: unpack")
+        dense = gpu.unpack([0])
+        want_dense = oracle_lib.unpack_accumulate(table, [want], n)
+        assert np.array_equal(dense.view(np.uint32), want_dense.view(np.uint32)), "decoded packet differs"
+    finally:
+        gpu.close()
