@@ -76,3 +76,15 @@ def test_largest_layer_the_abi_accepts(H, oracle_lib, L_T):
         assert np.array_equal(dense.view(np.uint32), want_dense.view(np.uint32)), "decoded packet differs"
     finally:
         gpu.close()
+
+
+def test_five_thousand_layers(H, oracle_lib):
+    """A table with thousands of small layers (the host's overlap check takes its sorted path above
+    512 layers; the header block of the placement kernel makes 20 rounds of 256 layers; every tile's
+    word offset sums over all layers before it): eager and lazy calls, three learners."""
+    rng = np.random.default_rng(5000)
+    lts = [1, 3, 50, 64, 65, 500, 1000, 4097]
+    layers = [(f"l{i}", int(rng.integers(1, 3000)), int(rng.choice(lts))) for i in range(5000)]
+    wl = W.custom("layers5000", layers, dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 2, seed=9, batch=True, check_gmax=False)
+    H.run_lazy_parity(oracle_lib, wl, 3, 3, 2, seed=10)
