@@ -88,3 +88,58 @@ def test_five_thousand_layers(H, oracle_lib):
     wl = W.custom("layers5000", layers, dist="normal_outliers")
     H.run_parity(oracle_lib, wl, 3, 2, seed=9, batch=True, check_gmax=False)
     H.run_lazy_parity(oracle_lib, wl, 3, 3, 2, seed=10)
+
+
+def test_layers_beyond_2_to_32_elements(H, oracle_lib):
+    """Layers that start beyond element 2^32 of the gradient buffer (offsets are 64-bit everywhere):
+    three layers, one near the start of a 26 GB buffer and two past 2^32, two learners, two
+    free-running batched steps and an unpack; the layers and a window around each are compared, and
+    nothing outside the layers may change."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.custom_placed("far", [("b", 50 * 4000 + 7, 50, 4096), ("a", 500 * 600 + 13, 500, 2 ** 32 + 4096),
+                                 ("c", 16384 * 6 + 5, 16384, 2 ** 32 + 2 ** 31)], dist="normal_outliers")
+    table, n_total = wl.table(), wl.n_total
+    assert n_total > 2 ** 32 + 2 ** 31
+    windows = [(max(0, off - 1024), min(n_total, off + n + 1024)) for off, n, _ in table]
+    gpu = G.GpuSide(table, n_total, 2, batch=True)
+    try:
+        g_dev = [torch.zeros(n_total, dtype=torch.float32, device=G.DEV) for _ in range(2)]
+        R_cpu = [np.zeros(n_total, f32) for _ in range(2)]    # untouched pages cost nothing
+        for r in gpu.residue:
+            r.fill_(7.0)                                        # outside the layers: must stay
+            for off, n, _ in table:
+                r[off:off + n] = 0.0
+        wants = []
+        for t in range(2):
+            G.say(f"far layers step {t}")
+            grads = [W.gradient(wl, k, t, seed=77) for k in range(2)]
+            for k in range(2):
+                for off, n, _ in table:
+                    g_dev[k][off:off + n].copy_(torch.from_numpy(grads[k][off:off + n]))
+            for p in gpu.packets:
+                p.fill_(G.POISON)
+            A.adacomp_compress_batch(table, g_dev, gpu.residue, gpu.packets, gpu.ws, packet_capacity=gpu.capacity)
+            torch.cuda.synchronize()
+            wants = [oracle_lib.compress(table, grads[k], R_cpu[k]) for k in range(2)]
+            for k in range(2):
+                G.compare_packet(gpu.packets[k].cpu().numpy(), wants[k], gpu.capacity, f"far layers step {t} learner {k}")
+                for (off, n, _), (lo, hi) in zip(table, windows):
+                    got = gpu.residue[k][lo:hi].cpu().numpy()
+                    want = np.full(hi - lo, 7.0, f32)
+                    want[off - lo:off - lo + n] = R_cpu[k][off:off + n]
+                    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"step {t} learner {k}: residue near {off}"
+        outside = n_total - sum(n for _, n, _ in table)
+        for k in range(2):   # nothing else was written: everything outside the layers is still 7
+            assert int((gpu.residue[k] == 7.0).sum()) == outside
+        G.say("far layers unpack")
+        gpu.dense.fill_(float("nan"))
+        A.adacomp_unpack_accumulate(table, gpu.packets, gpu.dense, gpu.ws)
+        torch.cuda.synchronize()
+        want_dense = oracle_lib.unpack_accumulate(table, wants, n_total)
+        for (off, n, _), (lo, hi) in zip(table, windows):
+            got = gpu.dense[lo:hi].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want_dense[lo:hi].view(np.uint32)), f"dense sum near {off}"
+        assert int(torch.isnan(gpu.dense).sum()) == outside
+    finally:
+        gpu.close()
