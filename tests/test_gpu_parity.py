@@ -587,6 +587,37 @@ def test_subnormal_and_large_magnitudes(H, oracle_lib):
     _update_case(oracle_lib, wl, 3, 2, 2, False, grads_fn=grads)
 
 
+def test_non_finite_inputs_are_memory_safe(H):
+    """NaN and infinities are outside the method (the results are unspecified), but the calls stay
+    inside their buffers: the packet is a well-formed container no longer than the bound, nothing is
+    written behind it or outside the layers, and the packet can be unpacked."""
+    import gpu_harness as G
+    import packet_format as pf
+    wl = W.custom("nonfinite", [("a", 50 * 90 + 7, 50), ("b", 500 * 20 + 11, 500), ("c", 16384 + 9, 16384)], dist="normal_outliers")
+    table, n = wl.table(), wl.n_total
+    mask = G.layer_mask(table, n)
+    gpu = G.GpuSide(table, n, 1)
+    try:
+        rng = np.random.default_rng(404)
+        for t in range(3):
+            g = W.gradient(wl, 0, t, seed=404)
+            bad = rng.choice(n, 400, replace=False)
+            g[bad[:150]] = np.nan
+            g[bad[150:275]] = np.inf
+            g[bad[275:]] = -np.inf
+            buf = gpu.compress(0, g)
+            h = pf.header(buf)
+            total = int(h["total_bytes"])
+            assert int(h["status"]) == 0 and total <= gpu.bound
+            assert np.all(buf[total:] == G.POISON)
+            pf.parse(buf[:total])                     # every structural invariant of the container
+            assert np.all(gpu.residue[0].cpu().numpy()[~mask] == 0)
+            dense = gpu.unpack([0])
+            assert np.isnan(dense[~mask]).all()
+    finally:
+        gpu.close()
+
+
 def test_all_zero_and_all_selected(H, oracle_lib):
     wl = W.custom("extremes", [("a", 50 * 70, 50), ("b", 500 * 9 + 100, 500)])
     n = wl.n_total
