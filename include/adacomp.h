@@ -277,6 +277,13 @@ int adacomp_selftest_binindex(void);
  * Returns ADACOMP_OK. */
 int adacomp_tuning_unpack_min_groups(uint32_t n_groups);
 
+/* Tuning knob of the compress calls, read at every call.  Tables of up to 512 compress tiles and
+ * 16 layers skip the separate scan launch (layer scales, word offsets): the placement kernel works
+ * them out itself.  enable = 0 makes such tables take the three-launch path of the large ones;
+ * non-zero restores the default.  Results do not depend on it.  Process-wide; not synchronised with
+ * calls on other threads.  Returns ADACOMP_OK. */
+int adacomp_tuning_fold_scan(int enable);
+
 /* Per-kernel timing of the streaming kernel (k_fused) of adacomp_compress / adacomp_compress_batch
  * with HIP events on the caller's stream.  enable = k > 0 starts recording every k-th launch (and
  * clears earlier records; an event pair costs a few microseconds between back-to-back launches, so

@@ -24,7 +24,7 @@ EXPORTS = [
     "adacomp_compress_batch_lazy", "adacomp_residue_sync",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
-    "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_timing_enable", "adacomp_timing_read",
+    "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_tuning_fold_scan", "adacomp_timing_enable", "adacomp_timing_read",
 ]
 
 PACKET_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("status", "<u4"), ("n_layers", "<u4"),
@@ -64,6 +64,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1712_02679_amd.build` "
                                "(there is no CPU fallback)")
+        # PyTorch brings its own copy of the HIP runtime; it has to be in the process before the
+        # library is, or the two end up with different runtimes and the first call that touches
+        # the device fails with ADACOMP_EHIP.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         LP, u32, sz, vp = ctypes.POINTER(Layer), ctypes.c_uint32, ctypes.c_size_t, ctypes.c_void_p
         for name in ("adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes"):
@@ -89,6 +93,7 @@ def lib():
         L.adacomp_debug_keep_gmax.argtypes = [ctypes.c_int]
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
         L.adacomp_tuning_unpack_min_groups.argtypes = [ctypes.c_uint32]
+        L.adacomp_tuning_fold_scan.argtypes = [ctypes.c_int]
         L.adacomp_timing_enable.argtypes = [ctypes.c_int]
         L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64),
                                           ctypes.POINTER(ctypes.c_uint64)]
@@ -247,6 +252,11 @@ def adacomp_selftest_binindex() -> int:
 def adacomp_tuning_unpack_min_groups(n_groups: int):
     """Workspaces initialised afterwards group unpack tiles only while n_groups workgroups remain; 0: default."""
     _check(lib().adacomp_tuning_unpack_min_groups(int(n_groups)))
+
+
+def adacomp_tuning_fold_scan(enable: bool):
+    """False: small tables take the three-launch compress path of the large ones; True: the default."""
+    _check(lib().adacomp_tuning_fold_scan(1 if enable else 0))
 
 
 def adacomp_timing_enable(every: int):

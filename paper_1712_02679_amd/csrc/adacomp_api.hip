@@ -60,6 +60,7 @@ static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
 }
 
 static uint32_t g_unpack_min_groups = kUnpackMinGroups;
+static bool g_fold_scan = true;
 
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &p)
 {
@@ -391,6 +392,12 @@ static uint32_t place_lanes_for(const Plan &p)
     return (p.has_short_bins || p.n_ctiles <= 2048u) ? 64u : 16u;
 }
 
+// Small tables: no k_scan launch, the placement kernel does the scan itself (see k_place).
+static bool fold_scan_for(const Plan &p)
+{
+    return g_fold_scan && place_lanes_for(p) == 64u && p.n_ctiles <= kFoldTiles && p.n_layers <= kFoldLayers;
+}
+
 static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
                            const float *const *grads, float *const *residues, void *const *packets_out,
                            size_t packet_capacity, uint32_t rule, float soft_factor, bool lazy, void *workspace,
@@ -440,6 +447,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.keep_gmax = g_keep_gmax ? 1u : 0u;
     a.class_tiles = (p.n_class_tiles[0] && p.n_class_tiles[1]) ? reinterpret_cast<const uint32_t *>(ws + p.ws.cclass) : nullptr;
     a.place_lanes = place_lanes_for(p);
+    a.fold_scan = fold_scan_for(p) ? 1u : 0u;
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;
@@ -482,7 +490,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
             }
             if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
         }
-        if ((rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
+        if (!a.fold_scan && (rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
         if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
     if (lazy) {
@@ -698,6 +706,12 @@ int adacomp_selftest_binindex(void)
 int adacomp_debug_keep_gmax(int enable)
 {
     g_keep_gmax = enable != 0;
+    return ADACOMP_OK;
+}
+
+int adacomp_tuning_fold_scan(int enable)
+{
+    g_fold_scan = enable != 0;
     return ADACOMP_OK;
 }
 

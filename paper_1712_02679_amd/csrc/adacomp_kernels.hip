@@ -13,7 +13,8 @@
 //            (tile-local index, sign) entries in a staging area, counts per bin go straight into
 //            the packet, g_max and its per-tile float64 sum go to scratch.
 //   k_scan   one workgroup per layer: the layer scale = average of the g_max vector (section
-//            "Pseudo code") and the exclusive scan of per-tile word counts.
+//            "Pseudo code") and the exclusive scan of per-tile word counts.  (Small tables: no
+//            launch; every k_place workgroup works these out itself.)
 //   k_place  16 or 64 lanes per tile: moves the staged entries to their final place in the packet
 //            as (index-in-bin, ternary code) words and applies the only step that needs the
 //            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
@@ -431,9 +432,25 @@ __device__ __forceinline__ uint64_t pad16_dev(uint64_t x) { return (x + 15u) & ~
 // the scratch block (staged entries, tile counts, layer scales) and the next lazy k_fused of this
 // learner applies them in registers, where they cost next to nothing; until then the residue holds
 // G at the sent elements.  kPlaceResidue applies waiting corrections and nothing else.
-template <uint32_t LANES, uint32_t MODE>
+// FOLD = true (small tables: up to kFoldTiles tiles and kFoldLayers layers; 64 lanes per tile): there
+// is no k_scan launch.  Every workgroup scans the word counts of all tiles itself (8 per thread, a
+// few kilobytes from L2) and every wave sums the g_max totals of its tile's layer, in one fixed
+// order (fold_layer_scale) that the header block uses as well; on tables that take 35-90 us per
+// step this is cheaper than a launch of 4 us and the gap before it.
+__device__ __forceinline__ float fold_layer_scale(const TileOut *tile_out, const uint32_t ctile_start,
+                                                  const uint32_t n_ctiles, const uint32_t n_bins, const uint32_t lane)
+{
+    double s = 0.0;
+    for (uint32_t t = lane; t < n_ctiles; t += 64u) s += tile_out[ctile_start + t].gmax_sum;
+    s = wave_sum_f64(s);          // lane 0 holds the sum
+    s = __shfl(s, 0, 64);
+    return float(s / double(n_bins));
+}
+
+template <uint32_t LANES, uint32_t MODE, bool FOLD>
 __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 {
+    static_assert(!FOLD || (LANES == 64u && MODE != kPlaceResidue), "the folded scan serves 64-lane placement launches");
     constexpr uint32_t kPlaceLanes = LANES, kPlaceTiles = kWG / LANES;
     const uint32_t tid = threadIdx.x;
     // per-learner buffers: blockIdx.y selects the learner of a batched call
@@ -446,13 +463,49 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     uint16_t *const stage_all = reinterpret_cast<uint16_t *>(sb + a.o_stage);
     uint8_t *const packet = a.packet[lr];
 
+    // s_excl[t] = words of all tiles before tile t (tile table order: layer after layer)
+    __shared__ uint32_t s_excl[FOLD ? kFoldTiles + 1u : 1u];
+    if (FOLD) {
+        __shared__ uint32_t s_fw[4];
+        constexpr uint32_t kPer = kFoldTiles / kWG;
+        const uint32_t lane = tid & 63u;
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        uint32_t cnt[kPer], sum = 0u;
+#pragma unroll
+        for (uint32_t i = 0; i < kPer; ++i) {
+            const uint32_t t = tid * kPer + i;
+            cnt[i] = t < a.n_tiles ? tile_out[t].count : 0u;
+            sum += cnt[i];
+        }
+        const uint32_t incl = wave_incl_scan(sum);
+        if (lane == 63u) s_fw[wave] = incl;
+        __syncthreads();
+        uint32_t run = incl - sum;
+        for (uint32_t wv = 0; wv < wave; ++wv) run += s_fw[wv];
+#pragma unroll
+        for (uint32_t i = 0; i < kPer; ++i) {
+            s_excl[tid * kPer + i] = run;
+            run += cnt[i];
+        }
+        if (tid == kWG - 1u) s_excl[kFoldTiles] = run;
+        __syncthreads();
+    }
+
     if (MODE == kPlaceResidue && blockIdx.x == gridDim.x - 1) return;
     if (MODE != kPlaceResidue && blockIdx.x == gridDim.x - 1) {
         // ---- header, layer records, zero padding: 256 layers at a time, word offsets by a block
         //      scan of the padded section sizes (all below 2^32: the packet bound is) --------------
         __shared__ uint32_t s_wtot[4];
+        __shared__ float s_fscale[FOLD ? kFoldLayers : 1u];
         const uint32_t lane = tid & 63u;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        if (FOLD) {
+            for (uint32_t l = wave; l < a.n_layers; l += 4u) {
+                const float sc = fold_layer_scale(tile_out, a.layers[l].ctile_start, a.layers[l].n_ctiles, a.layers[l].n_bins, lane);
+                if (lane == 0u) s_fscale[l] = sc;
+            }
+            __syncthreads();
+        }
         uint64_t carry = a.fixed_bytes, nsel_all = 0;
         for (uint32_t l0 = 0; l0 < a.n_layers; l0 += kWG) {
             const uint32_t l = l0 + tid;
@@ -462,8 +515,15 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
             float scale = 0.f;
             if (live) {
                 ld = a.layers[l];
-                nsel = layer_nsel[l];
-                scale = layer_scale[l];
+                if (FOLD) {   // and left in the scratch block for whoever applies the corrections later
+                    nsel = s_excl[ld.ctile_start + ld.n_ctiles] - s_excl[ld.ctile_start];
+                    scale = s_fscale[l];
+                    layer_nsel[l] = nsel;
+                    layer_scale[l] = scale;
+                } else {
+                    nsel = layer_nsel[l];
+                    scale = layer_scale[l];
+                }
                 bytes = uint32_t(pad16_dev(uint64_t(nsel) * ld.word_bytes));
             }
             const uint32_t incl = wave_incl_scan(bytes);
@@ -514,18 +574,24 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 
     // independent loads first: the tile's counters, its first staged entries, the layer's fields
     const TileOut to = tile_out[tile];
-    const uint32_t cnt = to.count, base = to.base;
+    const uint32_t cnt = to.count;
+    const uint32_t base = FOLD ? s_excl[tile] - s_excl[a.layers[l].ctile_start] : to.base;
     const uint16_t *__restrict__ stage = stage_all + td.elem_base;
     float *__restrict__ rs = a.residue[lr] + td.elem_base;
     const uint32_t s_first = stage[sub];  // speculative: the staging array has 64 entries of slack
-    const float scale = layer_scale[l];
+    const float scale = FOLD ? fold_layer_scale(tile_out, a.layers[l].ctile_start, a.layers[l].n_ctiles, a.layers[l].n_bins, sub)
+                             : layer_scale[l];
     const uint32_t wbytes = a.layers[l].word_bytes;
     const uint64_t chunks_offset = a.layers[l].chunks_offset;
     const uint32_t chunk_start = a.layers[l].chunk_start;
 
     // first word of this layer = end of the fixed part + the (padded) word sections before it
     uint64_t woff = 0;
-    for (uint32_t m = sub; m < l; m += kPlaceLanes) woff += pad16_dev(uint64_t(layer_nsel[m]) * a.layers[m].word_bytes);
+    for (uint32_t m = sub; m < l; m += kPlaceLanes) {
+        const uint32_t nsel_m = FOLD ? s_excl[a.layers[m].ctile_start + a.layers[m].n_ctiles] - s_excl[a.layers[m].ctile_start]
+                                     : layer_nsel[m];
+        woff += pad16_dev(uint64_t(nsel_m) * a.layers[m].word_bytes);
+    }
 #pragma unroll
     for (uint32_t d = kPlaceLanes / 2; d > 0; d >>= 1) {
         const uint32_t lo = __shfl_xor(uint32_t(woff), d, kPlaceLanes), hi = __shfl_xor(uint32_t(woff >> 32), d, kPlaceLanes);
@@ -983,16 +1049,21 @@ int launch_place(const CompressArgs &a, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 wg(kWG);
+    if (a.fold_scan && (a.place_lanes != 64u || a.place_mode == kPlaceResidue || a.n_tiles > kFoldTiles || a.n_layers > kFoldLayers))
+        return ADACOMP_EINVAL;  // the host picks the folded scan only where the kernel is built for it
     if (a.place_lanes == 64u) {
         const dim3 grid((a.n_tiles + 3u) / 4u + 1u, a.n_learners);
-        if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<64, kPlaceWords>), grid, wg, 0, s, a);
-        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<64, kPlaceResidue>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_place<64, kPlaceEager>), grid, wg, 0, s, a);
+        if (a.fold_scan) {
+            if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<64, kPlaceWords, true>), grid, wg, 0, s, a);
+            else hipLaunchKernelGGL((k_place<64, kPlaceEager, true>), grid, wg, 0, s, a);
+        } else if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<64, kPlaceWords, false>), grid, wg, 0, s, a);
+        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<64, kPlaceResidue, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_place<64, kPlaceEager, false>), grid, wg, 0, s, a);
     } else {
         const dim3 grid((a.n_tiles + 15u) / 16u + 1u, a.n_learners);
-        if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<16, kPlaceWords>), grid, wg, 0, s, a);
-        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<16, kPlaceResidue>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_place<16, kPlaceEager>), grid, wg, 0, s, a);
+        if (a.place_mode == kPlaceWords) hipLaunchKernelGGL((k_place<16, kPlaceWords, false>), grid, wg, 0, s, a);
+        else if (a.place_mode == kPlaceResidue) hipLaunchKernelGGL((k_place<16, kPlaceResidue, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_place<16, kPlaceEager, false>), grid, wg, 0, s, a);
     }
     return check_launch();
 }

@@ -12,6 +12,8 @@ namespace adacomp {
 
 constexpr uint32_t kWG = 256;            // threads per workgroup in every kernel (4 wave64)
 constexpr uint32_t kMaxTileBins = 1024;  // bins per compress tile (LDS arrays)
+constexpr uint32_t kFoldTiles = 512;     // tables up to this many compress tiles and
+constexpr uint32_t kFoldLayers = 16;     // this many layers: the placement kernel does the scan itself
 constexpr uint32_t kComputeUnits = 256;  // of an MI355X: what a small table's tiles are sized against
 // elements per unpack tile: 16 KB of LDS accumulators (8192 was 10 % faster for the plain sum but
 // 12 % slower with the optimizer epilogue)
@@ -136,6 +138,7 @@ struct CompressArgs {
     uint32_t class_first, class_count;  // this launch's stretch of class_tiles
     uint32_t place_lanes;               // lanes per tile in k_place: 16 or 64
     uint32_t place_mode;                // kPlaceEager / kPlaceWords / kPlaceResidue
+    uint32_t fold_scan;                 // no k_scan launch: k_place computes word offsets and layer scales itself
     uint32_t lazy;                      // k_fused applies the waiting residue corrections of the previous call
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2

@@ -155,6 +155,55 @@ def test_edge_tables(H, oracle_lib, name):
     H.run_parity(oracle_lib, wl, 3, 4, seed=7, label=name)
 
 
+@pytest.fixture
+def three_launch_compress():
+    """Small tables fold the scan into the placement kernel; this sends them down the path of the
+    large ones (separate scan launch) for the duration of a test."""
+    import paper_1712_02679_amd as A
+    A.adacomp_tuning_fold_scan(False)
+    yield
+    A.adacomp_tuning_fold_scan(True)
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_TABLES))
+def test_edge_tables_with_separate_scan_launch(H, oracle_lib, three_launch_compress, name):
+    wl = W.custom(name, EDGE_TABLES[name], dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 3, seed=8, label=name + ", separate scan", batch=True)
+    H.run_lazy_parity(oracle_lib, wl, 2, 3, 2, seed=8, label="lazy " + name + ", separate scan")
+
+
+def test_scan_paths_can_alternate(H, oracle_lib):
+    """The folded and the separate scan leave the same state behind: calls on one workspace may
+    alternate between them, also while lazy corrections wait."""
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.custom("alternate", [("a", 50 * 300 + 7, 50), ("b", 500 * 70 + 11, 500), ("c", 9000, 4500)], dist="normal_outliers")
+    table, n = wl.table(), wl.n_total
+    mask = G.layer_mask(table, n)
+    gpu = G.GpuSide(table, n, 2, batch=True)
+    R_cpu = [np.zeros(n, f32) for _ in range(2)]
+    try:
+        for t in range(8):
+            A.adacomp_tuning_fold_scan(t % 2 == 0)
+            grads = [W.gradient(wl, k, t, seed=12) for k in range(2)]
+            g_dev = [torch.from_numpy(x).to(G.DEV) for x in grads]
+            lazy = t % 4 < 3                           # three lazy calls, then an eager one after a sync
+            if lazy:
+                A.adacomp_compress_batch_lazy(table, g_dev, gpu.residue, gpu.packets, gpu.ws, packet_capacity=gpu.capacity)
+            else:
+                A.adacomp_residue_sync(gpu.ws)
+                A.adacomp_compress_batch(table, g_dev, gpu.residue, gpu.packets, gpu.ws, packet_capacity=gpu.capacity)
+            torch.cuda.synchronize()
+            for k in range(2):
+                want = oracle_lib.compress(table, grads[k], R_cpu[k])
+                assert np.array_equal(gpu.packets[k].cpu().numpy()[:want.size], want), f"step {t} learner {k}"
+                if not lazy:
+                    G.compare_residue(gpu.residue[k].cpu().numpy(), R_cpu[k], mask, 1.0, f"alternate step {t} learner {k}")
+    finally:
+        A.adacomp_tuning_fold_scan(True)
+        gpu.close()
+
+
 def test_layers_in_any_order_with_gaps(H, oracle_lib):
     """The layer table need not follow the buffer: layers listed out of address order, with large
     holes between them and in front of the first; nothing outside the layers is touched."""
