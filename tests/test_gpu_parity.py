@@ -979,6 +979,31 @@ def test_caller_written_in_c(H):
     assert "c caller ok" in res.stdout
 
 
+def test_library_called_before_torch_is_imported(H):
+    """A process that touches the binding before it imports torch must end up with one HIP runtime
+    (the binding pulls torch in before it loads the library): set-up and a compress call work."""
+    import subprocess
+    import sys
+    code = (
+        "import paper_1712_02679_amd as A\n"
+        "A.adacomp_tuning_fold_scan(True)\n"            # loads the library
+        "import torch\n"
+        "t = [(0, 50 * 40 + 7, 50), (2008, 500 * 12 + 11, 500)]\n"
+        "n = 2008 + 6011\n"
+        "ws = torch.zeros(A.adacomp_workspace_bytes(t), dtype=torch.uint8, device='cuda')\n"
+        "A.adacomp_workspace_init(t, ws)\n"
+        "g = torch.randn(n, device='cuda'); r = torch.zeros(n, device='cuda')\n"
+        "p = torch.zeros(A.adacomp_packet_bound(t), dtype=torch.uint8, device='cuda')\n"
+        "A.adacomp_compress(t, g, r, p, ws)\n"
+        "torch.cuda.synchronize()\n"
+        "h, _ = A.read_packet_summary(p)\n"
+        "assert int(h['n_selected']) > 0\n"
+        "print('ok')\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and "ok" in out.stdout, out.stderr[-2000:]
+
+
 def test_copy_kernel(H):
     import paper_1712_02679_amd as A
     for n in (1, 5, 1024, 1 << 20, (1 << 22) + 3):
