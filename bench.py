@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--learners", type=int, default=0, help="override the workload's learner count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
+    ap.add_argument("--no-lazy-leg", action="store_true", help="skip the extra leg through adacomp_compress_batch_lazy")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one step captured in a HIP graph (for the small, launch-bound workloads; "
                          "no roofline object, since events cannot be read back from a graph)")
@@ -265,6 +266,8 @@ def main():
     try:
         if args.no_batch:
             raise RuntimeError("needs the batched entry point")
+        if args.no_lazy_leg:
+            raise RuntimeError("skipped (--no-lazy-leg)")
         for r in residue:
             r.zero_()
         torch.cuda.synchronize()
