@@ -174,10 +174,16 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
         const float prev_scale = reinterpret_cast<const float *>(sb + a.o_layer_scale)[td.layer()];
         for (uint32_t i = tid; i < uint32_t(J) * 64u; i += kWG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
-        const uint16_t *prev_stage = stage_all + td.elem_base;
-        for (uint32_t p = tid; p < prev_count && p < n; p += kWG) {
-            const uint32_t entry = prev_stage[p];
-            if ((entry >> 2) < n) s_fix[entry >> 2] = uint8_t(entry & 3u);
+        // four entries per load: a tile's stretch of the staging area starts on an 8-byte boundary
+        // (tiles start at multiples of 4 elements) and what lies behind its last entry is readable
+        const uint2 *prev_stage = reinterpret_cast<const uint2 *>(stage_all + td.elem_base);
+        const uint32_t prev_n = prev_count < n ? prev_count : n;
+        for (uint32_t q = tid; 4u * q < prev_n; q += kWG) {
+            const uint2 v = prev_stage[q];
+            const uint32_t entry[4] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16};
+#pragma unroll
+            for (uint32_t i = 0; i < 4u; ++i)
+                if (4u * q + i < prev_n && (entry[i] >> 2) < n) s_fix[entry[i] >> 2] = uint8_t(entry[i] & 3u);
         }
         __syncthreads();
 #pragma unroll
