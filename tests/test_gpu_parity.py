@@ -947,6 +947,78 @@ def test_two_streams_two_workspaces(H, oracle_lib):
             s_.close()
 
 
+def test_two_host_threads_two_workspaces(H, oracle_lib):
+    """Two host threads call the library at the same time, each with its own stream, workspace and
+    learners (one through the eager calls, one through the lazy ones), while workspaces are
+    registered and released on a third: the host-side books are locked, and each thread gets exactly
+    what the oracle gives."""
+    import threading
+    import gpu_harness as G
+    import paper_1712_02679_amd as A
+    wl = W.workload(2)
+    table, n, nl, steps = wl.table(), wl.n_total, 2, 12
+    sides = [G.GpuSide(table, n, nl, batch=True) for _ in range(2)]
+    grads_np = [[[W.gradient(wl, 2 * w + k, t, seed=90) for k in range(nl)] for t in range(steps)] for w in range(2)]
+    grads = [[[torch.from_numpy(g).to(G.DEV) for g in step] for step in per] for per in grads_np]
+    packets = [[[torch.full((sides[w].capacity,), G.POISON, dtype=torch.uint8, device=G.DEV) for _ in range(nl)]
+                for _ in range(steps)] for w in range(2)]
+    torch.cuda.synchronize()
+    errors, stop = [], threading.Event()
+
+    def worker(w):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for t in range(steps):
+                    call = A.adacomp_compress_batch if w == 0 else A.adacomp_compress_batch_lazy
+                    call(table, grads[w][t], sides[w].residue, packets[w][t], sides[w].ws)
+                    A.adacomp_unpack_accumulate(table, packets[w][t], sides[w].dense, sides[w].ws)
+                if w == 1:
+                    A.adacomp_residue_sync(sides[w].ws)
+            stream.synchronize()
+        except Exception as e:   # reported by the main thread
+            errors.append((w, repr(e)))
+
+    def churn():
+        other = [(0, 5000, 50), (5000, 7001, 500)]
+        try:
+            while not stop.is_set():
+                ws = torch.zeros(A.adacomp_workspace_bytes(other), dtype=torch.uint8, device=G.DEV)
+                A.adacomp_workspace_init(other, ws)
+                A.adacomp_workspace_release(ws)
+        except Exception as e:
+            errors.append(("churn", repr(e)))
+
+    try:
+        threads = [threading.Thread(target=worker, args=(w,)) for w in range(2)]
+        extra = threading.Thread(target=churn)
+        extra.start()
+        for th in threads:
+            th.start()
+        for th in threads:
+            th.join()
+        stop.set()
+        extra.join()
+        torch.cuda.synchronize()
+        assert not errors, errors
+        mask = G.layer_mask(table, n)
+        for w in range(2):
+            R = [np.zeros(n, f32) for _ in range(nl)]
+            want = None
+            for t in range(steps):
+                want = [oracle_lib.compress(table, grads_np[w][t][k], R[k]) for k in range(nl)]
+                for k in range(nl):
+                    G.compare_packet(packets[w][t][k].cpu().numpy(), want[k], sides[w].capacity, f"thread {w} step {t} learner {k}")
+            for k in range(nl):
+                assert np.array_equal(sides[w].residue[k].cpu().numpy().view(np.uint32), R[k].view(np.uint32)), f"thread {w} residue {k}"
+            dense = oracle_lib.unpack_accumulate(table, want, n)
+            assert np.array_equal(sides[w].dense.cpu().numpy()[mask].view(np.uint32), dense[mask].view(np.uint32))
+    finally:
+        stop.set()
+        for s_ in sides:
+            s_.close()
+
+
 def test_checkpoint_resume(H, oracle_lib):
     """The residue is the only learner state: copying it out and back resumes identically."""
     import gpu_harness as G
