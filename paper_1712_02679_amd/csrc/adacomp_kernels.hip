@@ -100,16 +100,19 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 
 // ==============================================================================================
 // k_fused: Algorithm 2, both loops, on a tile of whole bins held in registers.
-// Thread t owns float4 slots t, t + 256, ...: element e = 4 * (j * 256 + t) + c of the tile.
+// Thread t owns float4 slots t, t + WG, ...: element e = 4 * (j * WG + t) + c of the tile, with WG = 256
+// threads and 4 slots each for tiles of 4096 elements, 1024 threads and 4 slots each for tiles of 16384.
 // ==============================================================================================
 // VARIANT = false is the method as built by default (union rule, factor 2: additions only);
 // VARIANT = true takes the selection rule and the soft-threshold factor from the arguments.
 // LAZY = true: the residue corrections of the learner's previous call (residue <- G - Gq at the
 // elements it sent) are still waiting in the scratch block instead of having been written (the host
 // knows); they are applied here, to the residue values in registers, before anything else.
-template <int J, bool VARIANT, bool LAZY>
-__global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
+template <int J, int WAVES, bool VARIANT, bool LAZY>
+__global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
 {
+    constexpr uint32_t WG = uint32_t(WAVES) * 64u;  // threads of the workgroup: a tile is J * WG float4 slots
+    static_assert(J * WAVES <= 64, "the per-row word totals are scanned by one wave");
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
     // call streams one learner's buffers after the other instead of all of them at once.  A launch
     // covers the class_count tiles of one register class (all tiles, for most tables).
@@ -133,14 +136,14 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     __shared__ uint32_t s_gmax[kMaxTileBins];  // bit pattern of max |G|: for non-negative floats the
     __shared__ uint32_t s_cnt[kMaxTileBins];   // unsigned integer order is the float order
     __shared__ uint32_t s_wtot[64];
-    __shared__ double s_red[4];
+    __shared__ double s_red[WAVES];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
     const uint32_t n = td.n_elems, T = td.L_T, M = td.magic, nb = td.n_bins;
     const bool vec = td.aligned();
 
-    for (uint32_t i = tid; i < nb; i += kWG) { s_gmax[i] = 0u; s_cnt[i] = 0u; }
+    for (uint32_t i = tid; i < nb; i += WG) { s_gmax[i] = 0u; s_cnt[i] = 0u; }
 
     const float *__restrict__ gr = a.grad[lr] + td.elem_base;
     float *__restrict__ rs = a.residue[lr] + td.elem_base;
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     float r[J][4], w[J][4];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
         if (vec && e0 + 4u <= n) {
             const vfloat4 rv = load_stream4(rs + e0);
             const vfloat4 wv = load_stream4(gr + e0);
@@ -169,16 +172,16 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
         // number and the layer's scale.  An entry becomes a code byte in LDS at the element's place;
         // every thread then reads the four codes of each of its slots and corrects its residues:
         // the same single float32 subtraction or addition that the eager placement performs.
-        __shared__ __attribute__((aligned(16))) uint8_t s_fix[J * 1024];
+        __shared__ __attribute__((aligned(16))) uint8_t s_fix[J * WG * 4];
         const uint32_t prev_count = tile_out[tile].count;
         const float prev_scale = reinterpret_cast<const float *>(sb + a.o_layer_scale)[td.layer()];
-        for (uint32_t i = tid; i < uint32_t(J) * 64u; i += kWG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
+        for (uint32_t i = tid; i < uint32_t(J) * WG / 4u; i += WG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
         // four entries per load: a tile's stretch of the staging area starts on an 8-byte boundary
         // (tiles start at multiples of 4 elements) and what lies behind its last entry is readable
         const uint2 *prev_stage = reinterpret_cast<const uint2 *>(stage_all + td.elem_base);
         const uint32_t prev_n = prev_count < n ? prev_count : n;
-        for (uint32_t q = tid; 4u * q < prev_n; q += kWG) {
+        for (uint32_t q = tid; 4u * q < prev_n; q += WG) {
             const uint2 v = prev_stage[q];
             const uint32_t entry[4] = {v.x & 0xFFFFu, v.x >> 16, v.y & 0xFFFFu, v.y >> 16};
 #pragma unroll
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < J; ++j) {
-            const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+            const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
             const uint32_t codes = *reinterpret_cast<const uint32_t *>(&s_fix[e0]);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     uint32_t mb[J][4];  // bits of max(|G|, |H|): what is compared with g_max
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
         float G[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     // ---- first loop of Algorithm 2: g_max(i) per bin -------------------------------------------
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
         if (e0 < n) {
             const uint32_t e3 = e0 + 3u < n ? e0 + 3u : n - 1u;
             const uint32_t b0 = bin_of(e0, T, M), b3 = bin_of(e3, T, M);
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     uint32_t wtot[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
         uint32_t f = 0u;
         if (e0 < n) {
 #pragma unroll
@@ -284,20 +287,20 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
         }
         before[j] = acc;
         wtot[j] = tot;
-        if (lane == 0) s_wtot[j * 4 + wave] = tot;
+        if (lane == 0) s_wtot[j * WAVES + wave] = tot;
     }
     __syncthreads();
 
     // element order inside the tile is (j, wave, lane, c): exclusive prefix over the 4 J rows
-    const uint32_t row_incl = wave_incl_scan(lane < uint32_t(4 * J) ? s_wtot[lane] : 0u);
-    const uint32_t tile_total = __shfl(row_incl, 4 * J - 1, 64);
+    const uint32_t row_incl = wave_incl_scan(lane < uint32_t(WAVES * J) ? s_wtot[lane] : 0u);
+    const uint32_t tile_total = __shfl(row_incl, WAVES * J - 1, 64);
 
     // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
     uint16_t *__restrict__ stage = stage_all + td.elem_base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * kWG + tid) * 4u;
-        uint32_t pos = __shfl(row_incl, j * 4 + int(wave), 64) - wtot[j] + before[j];
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        uint32_t pos = __shfl(row_incl, j * WAVES + int(wave), 64) - wtot[j] + before[j];
         const uint32_t f = flags[j];
         if (f) {
 #pragma unroll
@@ -318,14 +321,14 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     const LayerDev ld = a.layers[td.layer()];
     if (ld.word_bytes == 1u) {
         uint8_t *cp = packet + ld.counts_offset + td.first_bin;
-        for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint8_t(s_cnt[i]);
+        for (uint32_t i = tid; i < nb; i += WG) cp[i] = uint8_t(s_cnt[i]);
     } else {
         uint16_t *cp = reinterpret_cast<uint16_t *>(packet + ld.counts_offset) + td.first_bin;
-        for (uint32_t i = tid; i < nb; i += kWG) cp[i] = uint16_t(s_cnt[i]);
+        for (uint32_t i = tid; i < nb; i += WG) cp[i] = uint16_t(s_cnt[i]);
     }
     double part = 0.0;
     float *gm_out = gmax_out + ld.bin_start + td.first_bin;
-    for (uint32_t i = tid; i < nb; i += kWG) {
+    for (uint32_t i = tid; i < nb; i += WG) {
         const float g = __uint_as_float(s_gmax[i]);
         if (a.keep_gmax) gm_out[i] = g;  // diagnostics only: no later kernel reads the g_max vector
         part += double(g);
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     if (lane == 0) s_red[wave] = part;
     // running word count at every 64th bin of the layer that falls inside this tile
     const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
-    for (uint32_t t = t0 + 64u * wave; t < nb; t += 64u * 4u) {
+    for (uint32_t t = t0 + 64u * wave; t < nb; t += 64u * uint32_t(WAVES)) {
         uint32_t sum = 0u;
         for (uint32_t i = lane; i < t; i += 64u) sum += s_cnt[i];
         sum = wave_sum(sum);
@@ -343,7 +346,9 @@ __global__ __launch_bounds__(kWG) void k_fused(const CompressArgs a)
     __syncthreads();
     if (tid == 0) {
         TileOut o;
-        o.gmax_sum = ((s_red[0] + s_red[1]) + s_red[2]) + s_red[3];
+        double sum = s_red[0];
+        for (int wv = 1; wv < WAVES; ++wv) sum += s_red[wv];  // fixed order
+        o.gmax_sum = sum;
         o.count = tile_total;
         o.base = 0u;  // filled in by k_scan
         tile_out[tile] = o;  // one 16-byte store
@@ -1030,17 +1035,21 @@ static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK 
 int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(a.class_count * a.fused_count), wg(kWG);
+    // tiles of 4096 elements: 256 threads; tiles of 16384 (a bin longer than 4096): 1024 threads.  Either
+    // way a thread holds 16 elements, and a compute unit holds 32 waves of them.  (With 256 threads
+    // and 64 elements each the long-bin tiles had two workgroups per compute unit and streamed at
+    // 51-55 % of the HBM peak instead of 75-80 %.)
+    const dim3 grid(a.class_count * a.fused_count), wg(jcode == 0 ? 256 : 1024);
     const bool variant = a.rule != ADACOMP_RULE_ADACOMP || a.soft_factor_minus_1 != 1.0f;
     if (a.lazy) {  // the host offers lazy residues for the default method only
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false, true>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_fused<16, false, true>), grid, wg, 0, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, true>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<4, 16, false, true>), grid, wg, 0, s, a);
     } else if (!variant) {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, false, false>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_fused<16, false, false>), grid, wg, 0, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<4, 16, false, false>), grid, wg, 0, s, a);
     } else {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, true, false>), grid, wg, 0, s, a);
-        else hipLaunchKernelGGL((k_fused<16, true, false>), grid, wg, 0, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, true, false>), grid, wg, 0, s, a);
+        else hipLaunchKernelGGL((k_fused<4, 16, true, false>), grid, wg, 0, s, a);
     }
     return check_launch();
 }
