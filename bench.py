@@ -11,7 +11,9 @@ Prints ONE JSON line.  `value` = bytes of float32 gradient compressed and unpack
 streaming pass of compress) by its algorithmic bytes, 12 per element (read dW, read residue,
 write residue), against the MI355X's 8 TB/s HBM peak, with its duration measured by HIP events
 on the launch stream inside the timed region.  `cpu_baseline` times the CPU oracle, as it stands,
-on a bounded sample of the same workload.
+on a bounded sample of the same workload.  Beside these, never as `value`: `unpack_update` (the
+fused unpack + average + optimizer step) and `lazy_residue` (the same steps through
+adacomp_compress_batch_lazy, with the residue sync inside its timed region).
 """
 from __future__ import annotations
 
