@@ -423,7 +423,9 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     bool corrections_wait = false;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        const std::vector<float *> &waiting = g_ws[workspace].waiting;
+        auto it = g_ws.find(workspace);
+        if (it == g_ws.end()) return ADACOMP_EWORKSPACE;  // released by another thread meanwhile
+        const std::vector<float *> &waiting = it->second.waiting;
         if (!waiting.empty()) {
             if (!lazy || waiting.size() != n_learners) return ADACOMP_EPENDING;
             for (uint32_t k = 0; k < n_learners; ++k)
@@ -497,7 +499,8 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     }
     if (lazy) {
         std::lock_guard<std::mutex> lk(g_mu);
-        g_ws[workspace].waiting.assign(residues, residues + n_learners);
+        auto it = g_ws.find(workspace);
+        if (it != g_ws.end()) it->second.waiting.assign(residues, residues + n_learners);
     }
     return ADACOMP_OK;
 }
