@@ -28,15 +28,13 @@ _PROGRESS = None
 def say(msg):
     """Names the case about to run: on stdout (pytest shows it with -s or on failure) and, flushed, in
     a progress log that a test runner which captures stdout does not hide (in the directory
-    ADACOMP_TEST_LOG_DIR names, else in the run-output folder of the repository if there is one,
-    else in the temporary directory)."""
+    ADACOMP_TEST_LOG_DIR names, else in the temporary directory)."""
     global _PROGRESS
     print(f"[parity] {msg}", flush=True)
     try:
         if _PROGRESS is None:
             import tempfile
-            root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-            d = os.environ.get("ADACOMP_TEST_LOG_DIR") or os.path.join(root, "gpurun_out")
+            d = os.environ.get("ADACOMP_TEST_LOG_DIR") or ""
             if not os.path.isdir(d):
                 d = tempfile.gettempdir()
             _PROGRESS = open(os.path.join(d, "parity_progress.log"), "a", buffering=1)
