@@ -749,6 +749,23 @@ __device__ __forceinline__ void unpack_tables(const UnpackArgs &a, const LayerDe
     if (lane == 0) atomicMax(s_cmax, wmax);
 }
 
+// acc[idx] <- acc[idx] + v as an LDS load, a float add and an LDS store.  The LDS float atomic of
+// this GPU works through its active lanes one after the other (3 cycles per lane, measured: a wave
+// with all lanes busy holds the unit for 194 cycles, whatever the addresses), which made the adds
+// the bottleneck of the short-bin path.  The plain sequence is safe here: the words of one learner
+// name different elements, so no two lanes write one address in the same step; steps of different
+// learners that do meet on an address come from lanes of one wave in program order, and the LDS
+// unit executes a wave's instructions in order.  The accesses are volatile so that the compiler
+// keeps that order.  The sum, a single float32 addition per word, is the one the atomic gives.
+typedef __attribute__((address_space(3))) float lds_float;  // a float in LDS: ds_read / ds_write, not flat accesses
+__device__ __forceinline__ volatile lds_float *lds_volatile(float *p) { return (volatile lds_float *)p; }
+__device__ __forceinline__ void lds_add(float *acc, const uint32_t idx, const float v)
+{
+    volatile lds_float *p = lds_volatile(acc) + idx;
+    const float cur = *p;
+    *p = cur + v;
+}
+
 // Phase 2 for one tile: a lane group owns a bin (table row row0 + bin index inside the tile).
 template <bool W8>
 __device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev &ut, const uint32_t row0, const uint32_t k0,
@@ -797,19 +814,38 @@ __device__ __forceinline__ void unpack_adds(const UnpackArgs &a, const UTileDev 
                 __builtin_amdgcn_sched_barrier(0);  // one learner at a time: keeps the register count down
                 const uint32_t skew = off[kk] & 3u, cck = cc[kk];
                 const float sck = s_scale[h0 + kk];
+                // The words of this lane: bytes [beg, end) of its four, moved to the front so that
+                // slot j is in use in every lane that has more than j words and a slot that no lane
+                // of the wave uses costs nothing.  All loads of the accumulators first, then the
+                // stores (one learner's words name different elements).
+                volatile lds_float *vacc = lds_volatile(acc);
+                const uint32_t lo = 4u * sub, end_all = skew + cck;
+                const uint32_t beg = skew > lo ? (skew - lo < 4u ? skew - lo : 4u) : 0u;
+                const uint32_t end = end_all > lo ? (end_all - lo < 4u ? end_all - lo : 4u) : 0u;
+                const uint32_t nw = end > beg ? end - beg : 0u;
+                const uint32_t mine = beg < 4u ? packed[kk] >> (8u * beg) : 0u;
+                float cur[4];
+                uint32_t at_idx[4];
 #pragma unroll
                 for (uint32_t j = 0; j < 4u; ++j) {
-                    const uint32_t at = 4u * sub + j;  // byte of the fetched 16
-                    const uint32_t wd = (packed[kk] >> (8u * j)) & 0xFFu;
-                    const uint32_t idx = wd >> 2, code = wd & 3u;
-                    if (at >= skew && at - skew < cck && (code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
+                    at_idx[j] = 0xFFFFFFFFu;  // all ones: no word
+                    cur[j] = 0.f;
+                    if (__builtin_amdgcn_ballot_w64(j < nw) != 0ull) {
+                        const uint32_t wd = (mine >> (8u * j)) & 0xFFu;
+                        const uint32_t idx = wd >> 2, code = wd & 3u;
+                        const bool on = j < nw && (code & 1u) && idx < span;
+                        if (on) { at_idx[j] = idx | (code << 30); cur[j] = vacc[idx]; }  // code 1 or 3 in the top bits
+                    }
                 }
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j)
+                    if (at_idx[j] != 0xFFFFFFFFu) vacc[at_idx[j] & 0x3FFFFFFFu] = cur[j] + ((at_idx[j] >> 30) == 1u ? sck : -sck);
                 if (skew + cck > 16u) {  // the words of this learner beyond the fetched 16 bytes
                     const word_t *wp = reinterpret_cast<const word_t *>(a.packets[k0 + (h0 + kk < nk ? h0 + kk : 0u)]);
                     for (uint32_t q = 16u - skew + sub; q < cck; q += 4u) {
                         const uint32_t wd = wp[off[kk] + q];
                         const uint32_t idx = wd >> 2, code = wd & 3u;
-                        if ((code & 1u) && idx < span) atomicAdd(&acc[idx], code == 1u ? sck : -sck);
+                        if ((code & 1u) && idx < span) lds_add(acc, idx, code == 1u ? sck : -sck);
                     }
                 }
             }
