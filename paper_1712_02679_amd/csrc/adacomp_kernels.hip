@@ -238,6 +238,25 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        if (WAVES == 16) {
+            // Long bins: the 256 elements of a wave's row of slots nearly always lie in one bin, and
+            // 64 lanes that bring their maxima to one LDS address are served one after the other
+            // (2 cycles each, measured).  The wave reduces first; one lane goes to the LDS.
+            const uint32_t w0 = (uint32_t(j) * WG + wave * 64u) * 4u;   // uniform: first element of the row
+            if (w0 < n) {
+                const uint32_t w1 = w0 + 255u < n ? w0 + 255u : n - 1u;
+                const uint32_t bw = bin_of(w0, T, M);
+                if (bw == bin_of(w1, T, M)) {
+                    uint32_t m = gb[j][0] & 0x7FFFFFFFu;   // elements past n hold G = 0
+#pragma unroll
+                    for (int c = 1; c < 4; ++c) { const uint32_t v = gb[j][c] & 0x7FFFFFFFu; m = v > m ? v : m; }
+#pragma unroll
+                    for (uint32_t d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(m, d, 64); m = o > m ? o : m; }
+                    if (lane == 0) atomicMax(&s_gmax[bw], m);
+                    continue;
+                }
+            }
+        }
         if (e0 < n) {
             const uint32_t e3 = e0 + 3u < n ? e0 + 3u : n - 1u;
             const uint32_t b0 = bin_of(e0, T, M), b3 = bin_of(e3, T, M);
