@@ -686,10 +686,11 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 // up to 16 learners this is done once per run, which is what the runs are for: at L_T = 500 the
 // 8 tiles of a 64-bin chunk need the same count lines and the same prefix sums.  Phase 2, per
 // tile: a lane group per bin reads the 16 learners' table entries with a few wide LDS loads,
-// fetches the words of all 16 learners, and adds +-scale with LDS float atomics in learner order.
-// All adds to one address come from one wave in program order and the LDS unit executes a wave's
-// operations in order, so the sum order is fixed: learner 0 first.  (LDS float adds round to
-// nearest even and keep denormals, like v_add_f32.)  On the 125 M-element table with 16 learners
+// fetches the words of all 16 learners, and adds +-scale in learner order: with LDS float atomics
+// where bins are long and few lanes have a word, with plain LDS loads and stores where bins are
+// short (see lds_add).  All adds to one address come from one wave in program order and the LDS
+// unit executes a wave's operations in order, so the sum order is fixed: learner 0 first.  (LDS
+// float adds round to nearest even and keep denormals, like v_add_f32.)  On the 125 M-element table with 16 learners
 // a pass that only clears and writes the tiles takes 88 us, phase 1 per tile added 79 us and
 // phase 2 adds 63 us; sharing phase 1 over a run brought the whole launch from 230-250 to 185 us.
 // ==============================================================================================
