@@ -111,3 +111,13 @@ def test_no_cpu_fallback(L):
     base = (buf.ctypes.data + 255) // 256 * 256
     rc = L.adacomp_workspace_init(t, 1, ctypes.c_void_p(base), 1 << 15, None)
     assert rc == binding.EHIP
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert out.returncode != 0
+    assert "one GPU" in out.stderr and out.stdout.strip() == ""
