@@ -306,6 +306,43 @@ def pin_packet_structure_and_roundtrip(o):
     assert o.packet_bound(table) >= pk.size
 
 
+def pin_packet_bound_exact(o):
+    """The capacity that can never overflow, against byte counts worked out by hand from the
+    container layout (32-byte header, 64-byte record per layer, counts of 1 or 2 bytes per bin,
+    one 4-byte running count per 64 bins, words of 1 or 2 bytes, every section padded to 16), and
+    against a packet in which every element is sent, which has exactly that size."""
+    # the worked example's table: 16 elements, L_T 4 -> 4 bins, 8-bit words
+    #   32 + 64 | counts 4 -> 16 | chunks 4 -> 16 | words 16 -> 16
+    assert o.packet_bound([(0, 16, 4)]) == 96 + 16 + 16 + 16 == 144
+    # one layer with more than 64 bins: 6500 elements, L_T 50 -> 130 bins, 3 chunks
+    #   96 | counts 130 -> 144 | chunks 12 -> 16 | words 6500 -> 6512
+    assert o.packet_bound([(0, 6500, 50)]) == 96 + 144 + 16 + 6512 == 6768
+    # mixed word widths, every last bin short
+    table = [(0, 1003, 50),     # 21 bins:  counts 21 -> 32, chunks 4 -> 16, words 1003 -> 1008
+             (1004, 777, 500),  # 2 bins:   counts 4 -> 16,  chunks 16,      words 1554 -> 1568
+             (1784, 130, 64),   # 3 bins:   counts 3 -> 16,  chunks 16,      words 130 -> 144
+             (1916, 66, 65)]    # 2 bins:   counts 4 -> 16,  chunks 16,      words 132 -> 144
+    fixed = 32 + 4 * 64 + (32 + 16) + (16 + 16) + (16 + 16) + (16 + 16)
+    words = 1008 + 1568 + 144 + 144
+    assert fixed == 432 and words == 2864
+    assert o.packet_bound(table) == 3296
+    # every element sent (equal magnitudes: each one ties with its bin's maximum): the packet is
+    # exactly as long as the bound, and one byte less of capacity is refused
+    n_total = 1916 + 66
+    for tbl, n in [(table, n_total), ([(0, 16, 4)], 16), ([(0, 6500, 50)], 6500)]:
+        dW = np.where(np.arange(n) % 3 == 0, -0.25, 0.25).astype(f32)
+        pk = o.compress(tbl, dW, np.zeros(n, f32))
+        h, layers = pf.parse(pk)
+        assert int(h["n_selected"]) == sum(t[1] for t in tbl)
+        assert pk.size == o.packet_bound(tbl)
+        try:
+            o.compress(tbl, dW, np.zeros(n, f32), capacity=o.packet_bound(tbl) - 1)
+            raise AssertionError("a capacity one byte below the bound must not hold the all-sent packet")
+        except Exception as e:
+            assert getattr(e, "code", None) == -4
+    assert o.packet_bound([(0, 0, 50)]) == 0 and o.packet_bound([(0, 10, 0)]) == 0
+
+
 def pin_word_width_boundary(o):
     """8-bit words while the in-bin index fits 6 bits (L_T <= 64), 16-bit words above, up to
     L_T = 16384 where the index needs all 14 bits."""

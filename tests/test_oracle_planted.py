@@ -64,6 +64,11 @@ MUTANTS = {
     "unpack_ignores_bin": ("dense_out[layers[l].elem_offset + lo + j] += v;", "dense_out[layers[l].elem_offset + j] += v;"),
     "residue_committed_on_overflow": ("if (total > packet_capacity) { result = -4; goto done; }",
                                       "if (total > packet_capacity) { result = -4; for (uint32_t l = 0; l < n_layers; ++l) memcpy(residue + layers[l].elem_offset, tmp[l].R_new, layers[l].n_elems * sizeof(float)); goto done; }"),
+    "bound_doubled": ("return (size_t)off;", "return (size_t)(2 * off);"),
+    "bound_one_byte_per_element": ("off += pad16(layers[l].n_elems * (word_bits_of(layers[l].L_T) / 8));",
+                                   "off += pad16(layers[l].n_elems);"),
+    "bound_counts_one_byte_per_bin": ("off += pad16(n_bins * (word_bits_of(layers[l].L_T) / 8));", "off += pad16(n_bins);"),
+    "bound_without_chunk_table": ("off += pad16(n_chunks * 4);", "off += 0;"),
     "padding_not_zero": ("memset(pk, 0, (size_t)total);", "memset(pk, 0xAB, (size_t)total);"),
 }
 
