@@ -106,6 +106,21 @@ def workload(index: int) -> Workload:
     raise ValueError("workload index must be 1..5")
 
 
+def with_bin_lengths(wl: Workload, conv_L_T: int, fc_L_T: int, n_learners=None, n_steps=None) -> Workload:
+    """The same layer shapes, distributions and random draws as ``wl`` with other bin lengths: the
+    paper's stress tests keep the network and change only L_T (Fig. 2(a): 800 for convolutional
+    and 8000 for fully connected layers on the CIFAR10 CNN; section "Robustness of the AdaComp
+    Technique": 5000, and 200 / 300 for local selection).  Layers whose name starts with "conv" or
+    contains ".conv" / ".downsample" take conv_L_T, the others fc_L_T."""
+    def is_conv(name):
+        return name.startswith("conv") or ".conv" in name or ".downsample" in name
+    layers = tuple(Layer(l.name, l.n_elems, int(conv_L_T if is_conv(l.name) else fc_L_T), l.elem_offset)
+                   for l in wl.layers)
+    return Workload(wl.index, f"{wl.name}_LT{conv_L_T}_{fc_L_T}", layers,
+                    wl.n_learners if n_learners is None else n_learners,
+                    wl.n_steps if n_steps is None else n_steps, wl.dist)
+
+
 def custom(name, layers, n_learners=1, n_steps=1, dist="normal") -> Workload:
     """A workload over an arbitrary [(name, n_elems, L_T)] list (edge-case tests)."""
     return Workload(0, name, _place(layers), n_learners, n_steps, dist)

@@ -48,12 +48,15 @@ def say(msg):
 class GpuSide:
     """Device buffers of n learners for one layer table."""
 
-    def __init__(self, table, n_total, n_learners, capacity=None, batch=False):
+    def __init__(self, table, n_total, n_learners, capacity=None, batch=False, keep_gmax=False):
+        """keep_gmax: have compress store the g_max vector (a diagnostic that the timed path leaves
+        off); only the cases that compare it switch it on, and close() switches it off again."""
         self.table, self.n_total = table, n_total
         ws_bytes = A.adacomp_workspace_bytes_batch(table, n_learners) if batch else A.adacomp_workspace_bytes(table)
         self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV)
         A.adacomp_workspace_init(table, self.ws)
-        A.adacomp_debug_keep_gmax(True)   # the tests look at the g_max vector
+        self.keep_gmax = bool(keep_gmax)
+        A.adacomp_debug_keep_gmax(self.keep_gmax)
         self.bound = A.adacomp_packet_bound(table)
         self.capacity = self.bound if capacity is None else capacity
         self.residue = [torch.zeros(n_total, dtype=torch.float32, device=DEV) for _ in range(n_learners)]
@@ -89,11 +92,13 @@ class GpuSide:
         return self.dense.cpu().numpy()
 
     def gmax(self, learner=0):
+        assert self.keep_gmax, "this GpuSide was made without keep_gmax"
         off, n, stride = A.adacomp_workspace_gmax(self.table)
         off += stride * learner
         return self.ws[off:off + 4 * n].cpu().numpy().view(np.float32)
 
     def close(self):
+        A.adacomp_debug_keep_gmax(False)
         A.adacomp_workspace_release(self.ws)
 
 
@@ -151,7 +156,7 @@ def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, g
     assert batch or (rule == 0 and soft_factor == 2.0), "variants go through the batched entry point"
     table, n_total = wl.table(), wl.n_total
     mask = layer_mask(table, n_total)
-    gpu = GpuSide(table, n_total, n_learners, batch=batch)
+    gpu = GpuSide(table, n_total, n_learners, batch=batch, keep_gmax=check_gmax)
     R_cpu = [np.zeros(n_total, np.float32) for _ in range(n_learners)]
     stats = []
     try:

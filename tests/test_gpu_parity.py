@@ -47,14 +47,18 @@ def test_workload2_cifar_cnn_all_steps(H, oracle_lib):
     H.run_parity(oracle_lib, wl, wl.n_learners, wl.n_steps)
 
 
-def test_workload4_char_lstm(H, oracle_lib):
+def test_workload4_char_lstm_single_calls(H, oracle_lib):
     wl = W.workload(4)
-    H.run_parity(oracle_lib, wl, wl.n_learners, 6, check_gmax=False)   # 8 learners, first 6 of 50 steps
+    H.run_parity(oracle_lib, wl, wl.n_learners, 3)   # 8 learners, one adacomp_compress call each, g_max compared
 
 
-def test_workload4_char_lstm_long_run_one_learner(H, oracle_lib):
+def test_workload4_as_configured(H, oracle_lib):
+    """The char-LSTM table exactly as configured: 8 learners x 50 free-running steps through
+    adacomp_compress_batch and adacomp_unpack_accumulate, in the launch configuration bench.py times
+    (no g_max vector kept); every packet, residue and 8-packet sum of every step against the oracle."""
     wl = W.workload(4)
-    H.run_parity(oracle_lib, wl, 1, wl.n_steps, check_gmax=False, unpack_every_step=False)  # all 50 steps
+    assert (wl.n_learners, wl.n_steps) == (8, 50)
+    H.run_parity(oracle_lib, wl, wl.n_learners, wl.n_steps, batch=True, check_gmax=False, threads=16, oracle_threads=8)
 
 
 def test_workload2_long_run(H, oracle_lib):
@@ -118,7 +122,7 @@ def test_worked_example_on_gpu(H, oracle_lib):
     wl = W.custom("worked", [("l", 16, 4)])
     import gpu_harness as G
     import packet_format as pf
-    gpu = G.GpuSide(wl.table(), 16, 1)
+    gpu = G.GpuSide(wl.table(), 16, 1, keep_gmax=True)
     try:
         gpu.residue[0].copy_(torch.from_numpy(R0))
         buf = gpu.compress(0, dW)
@@ -256,11 +260,6 @@ def test_batch_workload2(H, oracle_lib):
     H.run_parity(oracle_lib, wl, wl.n_learners, 6, batch=True)
 
 
-def test_batch_workload4_eight_learners(H, oracle_lib):
-    wl = W.workload(4)
-    H.run_parity(oracle_lib, wl, wl.n_learners, 3, batch=True, check_gmax=False)
-
-
 def test_batch_workload3_all_learners_all_steps(H, oracle_lib):
     """ResNet-50 table as configured: 8 learners, 10 free-running steps, one batched call per step."""
     wl = W.workload(3)
@@ -278,12 +277,14 @@ def test_batch_more_learners_than_one_launch_holds(H, oracle_lib):
     H.run_parity(oracle_lib, wl, 40, 2, seed=3, batch=True, check_gmax=False)
 
 
-def test_batch_workload5_sixteen_learners_free_running(H, oracle_lib):
-    """The configuration bench.py times, free-running: 16 learners of the 125 M-element table, three
-    steps of adacomp_compress_batch and a 16-packet unpack after each, every packet, residue and sum
-    against the oracle."""
+def test_workload5_as_configured(H, oracle_lib):
+    """The speech-DNN table exactly as configured and as bench.py times it: 16 learners of the
+    125 M-element table, 10 free-running steps of adacomp_compress_batch (no g_max vector kept) with a
+    16-packet adacomp_unpack_accumulate after each; every packet, residue and sum of every step against
+    the oracle (one oracle call per learner and host thread)."""
     wl = W.workload(5)
-    H.run_parity(oracle_lib, wl, 16, 3, batch=True, check_gmax=False, threads=16, oracle_threads=16)
+    assert (wl.n_learners, wl.n_steps) == (16, 10)
+    H.run_parity(oracle_lib, wl, wl.n_learners, wl.n_steps, batch=True, check_gmax=False, threads=16, oracle_threads=16)
 
 
 def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
@@ -323,6 +324,25 @@ def test_batch_workload5_full_size_sixteen_learners(H, oracle_lib):
             single.close()
     finally:
         gpu.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# the paper's own stress-test bin lengths on the CIFAR10-CNN table
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("conv_lt,fc_lt", [(800, 8000), (5000, 5000)])
+def test_paper_stress_bin_lengths(H, oracle_lib, conv_lt, fc_lt):
+    """Fig. 2(a): L_T = 800 for convolutional and 8000 for fully connected layers; section
+    "Robustness of the AdaComp Technique": L_T = 5000 everywhere.  4 learners x 5 free-running steps."""
+    wl = W.with_bin_lengths(W.workload(2), conv_lt, fc_lt)
+    H.run_parity(oracle_lib, wl, 4, 5, batch=True)
+
+
+@pytest.mark.parametrize("lt", [200, 300])
+def test_paper_local_selection_bin_lengths(H, oracle_lib, lt):
+    """Section "Robustness of the AdaComp Technique": local selection (bin maxima only) at the bin
+    lengths of its ablation, 200 and 300, 4 learners x 5 free-running steps."""
+    wl = W.with_bin_lengths(W.workload(2), lt, lt)
+    H.run_parity(oracle_lib, wl, 4, 5, batch=True, rule=2)
 
 
 # ------------------------------------------------------------------------------------------------
