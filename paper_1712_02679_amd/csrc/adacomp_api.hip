@@ -23,15 +23,6 @@ uint32_t bin_magic(uint32_t L_T)
     return L_T <= 1 ? 0u : uint32_t((uint64_t(1) << 32) / L_T) + 1u;
 }
 
-uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers)
-{
-    uint64_t h = 1469598103934665603ull;  // FNV-1a over the fields that matter
-    auto mix = [&h](uint64_t v) { for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xFF; h *= 1099511628211ull; } };
-    mix(n_layers);
-    for (uint32_t l = 0; l < n_layers; ++l) { mix(layers[l].elem_offset); mix(layers[l].n_elems); mix(layers[l].L_T); }
-    return h;
-}
-
 static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
 {
     if (!layers || n_layers == 0 || n_layers >= (1u << 24)) return ADACOMP_EINVAL;
@@ -68,7 +59,6 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     if (rc != ADACOMP_OK) return rc;
     p = Plan();
     p.n_layers = n_layers;
-    p.table_hash = hash_table(layers, n_layers);
     p.layers.resize(n_layers);
 
     uint64_t fixed = sizeof(adacomp_packet_header_t) + uint64_t(sizeof(adacomp_packet_layer_t)) * n_layers;
@@ -264,19 +254,36 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
 // waiting: the residue buffers, by learner slot, whose corrections of the last lazy call have not
 // been written yet (empty: none).  Kept at enqueue time, which is stream order for a workspace that
 // one stream uses at a time.
-struct Registered { Plan plan; size_t bytes = 0; std::vector<float *> waiting; };
+struct Registered {
+    Plan plan;
+    size_t bytes = 0;
+    std::vector<adacomp_layer_t> table;  // the layer table the tile tables in the workspace were built for
+    std::vector<float *> waiting;
+};
+
+static bool same_table(const std::vector<adacomp_layer_t> &have, const adacomp_layer_t *layers, uint32_t n_layers)
+{
+    if (have.size() != n_layers) return false;
+    for (uint32_t l = 0; l < n_layers; ++l)
+        if (have[l].elem_offset != layers[l].elem_offset || have[l].n_elems != layers[l].n_elems ||
+            have[l].L_T != layers[l].L_T)
+            return false;
+    return true;
+}
 static std::mutex g_mu;
 static std::unordered_map<const void *, Registered> g_ws;
 
-static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace,
-                     size_t workspace_bytes, size_t n_learners, Plan &out)
+int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace,
+              size_t workspace_bytes, size_t n_learners, Plan &out)
 {
     if (!layers || n_layers == 0 || !workspace) return ADACOMP_EINVAL;
     std::lock_guard<std::mutex> lk(g_mu);
     auto it = g_ws.find(workspace);
     if (it == g_ws.end()) return ADACOMP_EWORKSPACE;
     const Plan &p = it->second.plan;
-    if (p.n_layers != n_layers || p.table_hash != hash_table(layers, n_layers)) return ADACOMP_EWORKSPACE;
+    // the kernels index the tile tables in the workspace without further checks: the table of this
+    // call must be, entry by entry, the one those tables were built for
+    if (!same_table(it->second.table, layers, n_layers)) return ADACOMP_EWORKSPACE;
     if (workspace_bytes < p.ws.total(n_learners) || it->second.bytes < p.ws.total(n_learners)) return ADACOMP_EWORKSPACE;
     // copy the scalars only; the tables already live on the device
     out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles; out.n_ugroups = p.n_ugroups; out.n_ugroups8 = p.n_ugroups8; out.n_usingles8 = p.n_usingles8;
@@ -285,8 +292,26 @@ static int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const voi
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
     for (int c = 0; c < 2; ++c) out.n_class_tiles[c] = p.n_class_tiles[c];
     out.has_short_bins = p.has_short_bins;
-    out.table_hash = p.table_hash; out.ws = p.ws;
+    out.ws = p.ws;
     return ADACOMP_OK;
+}
+
+void register_workspace(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace, size_t workspace_bytes,
+                        Plan &&plan)
+{
+    Registered reg;
+    reg.plan = std::move(plan);
+    Plan &p = reg.plan;
+    // the host copies of the tile tables are not needed once they are on the device
+    p.ctiles.clear(); p.ctiles.shrink_to_fit();
+    p.cclass.clear(); p.cclass.shrink_to_fit();
+    p.utiles.clear(); p.utiles.shrink_to_fit();
+    p.ugroups.clear(); p.ugroups.shrink_to_fit();
+    p.usingles.clear(); p.usingles.shrink_to_fit();
+    reg.table.assign(layers, layers + n_layers);
+    reg.bytes = workspace_bytes;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_ws[workspace] = std::move(reg);
 }
 
 // ---- optional event timing of the streaming kernel ---------------------------------------------
@@ -365,15 +390,7 @@ int adacomp_workspace_init(const adacomp_layer_t *layers, uint32_t n_layers, voi
         hipMemcpy(ws + p.ws.ugroups, p.ugroups.data(), sizeof(UGroupDev) * p.ugroups.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(ws + p.ws.usingles, p.usingles.data(), sizeof(UGroupDev) * p.usingles.size(), hipMemcpyHostToDevice) != hipSuccess)
         return ADACOMP_EHIP;
-    // the host copies of the tile tables are no longer needed
-    p.ctiles.clear(); p.ctiles.shrink_to_fit();
-    p.cclass.clear(); p.cclass.shrink_to_fit();
-    p.utiles.clear(); p.utiles.shrink_to_fit();
-    p.ugroups.clear(); p.ugroups.shrink_to_fit();
-    p.usingles.clear(); p.usingles.shrink_to_fit();
-    std::lock_guard<std::mutex> lk(g_mu);
-    reg.bytes = workspace_bytes;
-    g_ws[workspace] = std::move(reg);
+    register_workspace(layers, n_layers, workspace, workspace_bytes, std::move(reg.plan));
     return ADACOMP_OK;
 }
 

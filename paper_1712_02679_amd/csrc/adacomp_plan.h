@@ -109,7 +109,6 @@ struct Plan {
     uint32_t n_class_tiles[2] = {0, 0};  // compress tiles of 4096 / of 16384 elements
     std::vector<uint32_t> cclass;        // compress tile indices, the 4096-element ones first (tables with both kinds)
     bool has_short_bins = false;  // some layer has L_T <= 64 (8-bit words, many words per tile)
-    uint64_t table_hash = 0;
     WorkspaceLayout ws;
     std::vector<LayerDev> layers;
     std::vector<TileDev> ctiles;
@@ -119,8 +118,14 @@ struct Plan {
 
 // Validates the table (ADACOMP_E* on failure) and, with tables = true, fills the tile tables.
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &plan);
-uint64_t hash_table(const adacomp_layer_t *layers, uint32_t n_layers);
 uint32_t bin_magic(uint32_t L_T);
+// Host bookkeeping of adacomp_workspace_init (which workspace holds the tile tables of which layer
+// table) and the look-up every compute call starts with: ADACOMP_EWORKSPACE unless `workspace` was
+// registered for exactly this list of layers and is large enough for n_learners scratch blocks.
+void register_workspace(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace, size_t workspace_bytes,
+                        Plan &&plan);
+int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *workspace, size_t workspace_bytes,
+              size_t n_learners, Plan &out);
 
 // ---- kernel launchers (adacomp_kernels.hip) ---------------------------------------------------
 constexpr uint32_t kMaxBatch = 32;  // learners per launch of the compress kernels

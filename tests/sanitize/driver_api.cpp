@@ -177,6 +177,37 @@ int main()
         for (const auto &g : p.ugroups) longest = g.n_tiles > longest ? g.n_tiles : longest;
         if (longest != adacomp::kUnpackGroupTiles || p.ugroups.back().n_tiles != 1) return 11;
     }
+    {   // a workspace registered for one layer table serves that list of layers and no other: the
+        // same table is found, tables of the same length that differ in one field of one layer are
+        // refused (the kernels would index the tile tables of the wrong geometry otherwise)
+        using namespace adacomp;
+        std::vector<adacomp_layer_t> a = {{0, 5000, 50, 0}, {5000, 70000, 500, 0}, {75000, 130, 64, 0}};
+        alignas(256) static char fake_ws[256];
+        Plan p, found;
+        if (build_plan(a.data(), 3, true, p) != ADACOMP_OK) return 20;
+        const size_t bytes = p.ws.total(2);
+        register_workspace(a.data(), 3, fake_ws, bytes, std::move(p));
+        if (find_plan(a.data(), 3, fake_ws, bytes, 2, found) != ADACOMP_OK) return 21;
+        if (found.n_ctiles == 0 || found.ws.total(2) != bytes) return 22;
+        if (find_plan(a.data(), 3, fake_ws, bytes, 3, found) != ADACOMP_EWORKSPACE) return 23;  // too small for 3 learners
+        if (find_plan(a.data(), 3, fake_ws + 16, bytes, 2, found) != ADACOMP_EWORKSPACE) return 24;
+        for (int field = 0; field < 3; ++field)
+            for (int l = 0; l < 3; ++l) {
+                std::vector<adacomp_layer_t> b = a;
+                if (field == 0) b[l].L_T += 1;
+                if (field == 1) b[l].n_elems -= 1;
+                if (field == 2) b[2].elem_offset += 4 * (l + 1);   // the last layer moved up: still no overlap
+                if (adacomp_packet_bound(b.data(), 3) == 0) return 25;   // b is a valid table in its own right
+                if (find_plan(b.data(), 3, fake_ws, bytes, 2, found) != ADACOMP_EWORKSPACE) return 26;
+                const float *g = reinterpret_cast<const float *>(fake_ws);
+                if (adacomp_compress(b.data(), 3, g + 4, const_cast<float *>(g) + 8, fake_ws + 64, 1 << 20, fake_ws, bytes, nullptr) !=
+                    ADACOMP_EWORKSPACE)
+                    return 27;
+            }
+        if (find_plan(a.data(), 2, fake_ws, bytes, 2, found) != ADACOMP_EWORKSPACE) return 28;  // a prefix of the list
+        if (adacomp_workspace_release(fake_ws) != ADACOMP_OK) return 29;
+        if (find_plan(a.data(), 3, fake_ws, bytes, 2, found) != ADACOMP_EWORKSPACE) return 30;
+    }
     if (adacomp_selftest_binindex() != 0) return 9;
     for (int c = 1; c > -9; --c) if (!adacomp_strerror(c)) return 10;
     std::printf("api sanitizer driver ok, checksum %llu, %llu tiles and %llu groups checked\n", (unsigned long long)checksum,
