@@ -64,6 +64,8 @@ extern "C" {
 #define ADACOMP_EPENDING (-7)   /* residue corrections of a lazy call wait in this workspace and the call
                                    is not the lazy call that goes on with the same residue buffers      */
 
+#define ADACOMP_ETOOBIG (-8)    /* adacomp_compress_static: the table needs more than ADACOMP_STATIC_SCRATCH_BYTES */
+
 #define ADACOMP_LT_MAX 16384u
 #define ADACOMP_CHUNK_BINS 64u
 #define ADACOMP_PACKET_MAGIC 0x50434441u /* bytes 'A' 'D' 'C' 'P' */
@@ -139,6 +141,30 @@ int adacomp_workspace_release(void *workspace);
 int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
                      float *residue, void *packet_out, size_t packet_capacity, void *workspace,
                      size_t workspace_bytes, void *hip_stream);
+
+/* adacomp_compress for callers that cannot allocate device memory or hand in a workspace: code
+ * that runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error codes as adacomp_compress (packet and residue are bit for bit the
+ * same), but the workspace is an array of ADACOMP_STATIC_SCRATCH_BYTES (16 MiB) that the library
+ * holds in the memory of every GPU it runs on until the process ends; there is no
+ * adacomp_workspace_init to call.  No device memory is allocated or freed by this call, or by
+ * anything it calls.
+ *   - A layer table whose adacomp_workspace_bytes exceeds the array (about 2.1 bytes per gradient
+ *     element: tables beyond roughly 7.5 M elements) is refused with ADACOMP_ETOOBIG before
+ *     anything is enqueued.
+ *   - The first call on a device, and every call whose layer table differs from the previous
+ *     call's on that device, writes the tile tables into the array with blocking host-to-device
+ *     copies ordered after the work already on hip_stream (so that call is not capturable in a
+ *     graph and waits for the stream); calls that repeat the table only launch kernels and touch
+ *     no allocator, host or device.
+ *   - All calls on one GPU share that GPU's array, which keeps what the last call left in it.
+ *     Nothing in it has to start at zero (every field a kernel reads is written earlier in the
+ *     same call), but two calls that overlap in time on one GPU (different streams, different
+ *     threads) race on it: give them one stream, or use adacomp_compress with workspaces of the
+ *     caller's. */
+#define ADACOMP_STATIC_SCRATCH_BYTES (16u << 20)
+int adacomp_compress_static(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad,
+                            float *residue, void *packet_out, size_t packet_capacity, void *hip_stream);
 
 /* pack() for several learners that share one layer table, in one set of launches (the simulated
  * learners of a single-GPU run, or several model replicas on one device).  grads, residues and

@@ -15,12 +15,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadacomp.so")
 
-OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE, EPENDING = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EBADLT, EALIGN, ENOSPC, EHIP, EWORKSPACE, EPENDING, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
+STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = [
     "adacomp_packet_bound", "adacomp_packet_fixed_bytes", "adacomp_workspace_bytes",
     "adacomp_workspace_bytes_batch", "adacomp_workspace_init", "adacomp_workspace_release",
-    "adacomp_compress", "adacomp_compress_batch", "adacomp_compress_variant",
+    "adacomp_compress", "adacomp_compress_static", "adacomp_compress_batch", "adacomp_compress_variant",
     "adacomp_compress_batch_lazy", "adacomp_residue_sync",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
@@ -84,6 +85,7 @@ def lib():
         L.adacomp_workspace_init.argtypes = [LP, u32, vp, sz, vp]
         L.adacomp_workspace_release.argtypes = [vp]
         L.adacomp_compress.argtypes = [LP, u32, vp, vp, vp, sz, vp, sz, vp]
+        L.adacomp_compress_static.argtypes = [LP, u32, vp, vp, vp, sz, vp]
         L.adacomp_unpack_accumulate.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, sz, vp]
         L.adacomp_unpack_update.argtypes = [LP, u32, ctypes.POINTER(vp), u32, vp, vp, vp, vp,
                                             ctypes.POINTER(Optimizer), vp, sz, vp]
@@ -160,6 +162,13 @@ def adacomp_compress(layers, grad, residue, packet_out, workspace, packet_capaci
     _check(lib().adacomp_compress(layer_array(layers), len(layers), _ptr(grad), _ptr(residue),
                                   _ptr(packet_out), cap, _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream()))
+
+
+def adacomp_compress_static(layers, grad, residue, packet_out, packet_capacity=None):
+    """adacomp_compress on the library's own static scratch array: no workspace, nothing allocated."""
+    cap = packet_out.numel() if packet_capacity is None else int(packet_capacity)
+    _check(lib().adacomp_compress_static(layer_array(layers), len(layers), _ptr(grad), _ptr(residue),
+                                         _ptr(packet_out), cap, _stream()))
 
 
 def adacomp_compress_batch(layers, grads, residues, packets_out, workspace, packet_capacity=None):

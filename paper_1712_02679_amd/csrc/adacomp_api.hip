@@ -597,6 +597,56 @@ int adacomp_compress(const adacomp_layer_t *layers, uint32_t n_layers, const flo
                                   workspace, workspace_bytes, hip_stream);
 }
 
+// ---- the entry point that allocates nothing -----------------------------------------------------
+// Its workspace is a file-scope device array.  Host code never uses the array's name as an address
+// (on the host the name is only a handle for the runtime): the device address of this GPU's copy
+// comes from hipGetSymbolAddress, once per device, and that pointer is what is registered as the
+// workspace, copied to and handed to the kernels.
+constexpr size_t kStaticScratchBytes = ADACOMP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static void *g_static_ptr[kMaxDevices];  // per device: where that device holds `scratch`
+
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ADACOMP_EHIP;
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (!g_static_ptr[dev]) {   // first call on this device, which is current
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ADACOMP_EHIP;
+        if (reinterpret_cast<uintptr_t>(ptr) % 256 != 0) return ADACOMP_EALIGN;
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return ADACOMP_OK;
+}
+
+int adacomp_compress_static(const adacomp_layer_t *layers, uint32_t n_layers, const float *grad, float *residue,
+                            void *packet_out, size_t packet_capacity, void *hip_stream)
+{
+    if (!layers || n_layers == 0 || !grad || !residue || !packet_out) return ADACOMP_EINVAL;
+    void *ws = nullptr;
+    const int rc_dev = static_scratch(&ws);
+    if (rc_dev == ADACOMP_OK) {
+        // the usual case: this device's array already holds the tile tables of this layer table
+        const int rc = adacomp_compress(layers, n_layers, grad, residue, packet_out, packet_capacity, ws,
+                                        kStaticScratchBytes, hip_stream);
+        if (rc != ADACOMP_EWORKSPACE) return rc;
+    }
+    // another layer table than the last call's on this device (or the first call): check it, see that
+    // it fits, and write its tile tables into the array
+    Plan p;
+    int rc = build_plan(layers, n_layers, false, p);
+    if (rc != ADACOMP_OK) return rc;
+    if (p.ws.total(1) > kStaticScratchBytes) return ADACOMP_ETOOBIG;
+    if (rc_dev != ADACOMP_OK) return rc_dev;
+    if ((rc = adacomp_workspace_init(layers, n_layers, ws, kStaticScratchBytes, hip_stream)) != ADACOMP_OK) return rc;
+    return adacomp_compress(layers, n_layers, grad, residue, packet_out, packet_capacity, ws, kStaticScratchBytes,
+                            hip_stream);
+}
+
 static int unpack_common(const adacomp_layer_t *layers, uint32_t n_layers, const void *const *packets,
                          uint32_t n_learners, float *dense_out, float *weights, float *state1, float *state2,
                          const adacomp_optimizer_t *opt, void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -701,6 +751,7 @@ const char *adacomp_strerror(int code)
     case ADACOMP_EHIP: return "HIP runtime error (no device or failed launch)";
     case ADACOMP_EWORKSPACE: return "workspace too small or not initialised for this layer table";
     case ADACOMP_EPENDING: return "residue corrections of a lazy call wait in this workspace: go on with the same lazy call or call adacomp_residue_sync";
+    case ADACOMP_ETOOBIG: return "layer table needs more workspace than the static scratch array holds (16 MiB): use adacomp_compress with a workspace of the caller's";
     default: return "unknown adacomp error";
     }
 }

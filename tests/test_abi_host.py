@@ -101,6 +101,27 @@ def test_error_codes_without_touching_the_gpu(L):
     assert b"L_T" in L.adacomp_strerror(binding.EBADLT)
 
 
+def test_static_entry_point_refusals_need_no_gpu(L):
+    """adacomp_compress_static: null pointers, bad tables and tables beyond the static array are
+    refused on the host; a table that fits fails loudly without a GPU (no CPU path)."""
+    import torch
+    buf = np.zeros(1 << 16, np.uint8)
+    base = (buf.ctypes.data + 255) // 256 * 256
+    p = ctypes.c_void_p
+    t = binding.layer_array([(0, 1000, 50)])
+    assert L.adacomp_compress_static(t, 1, None, p(base + 4096), p(base + 8192), 4096, None) == binding.EINVAL
+    assert L.adacomp_compress_static(None, 1, p(base), p(base + 4096), p(base + 8192), 4096, None) == binding.EINVAL
+    if torch.cuda.is_available():
+        return   # the rest would enqueue work on host pointers
+    bad = binding.layer_array([(0, 1000, 16385)])
+    assert L.adacomp_compress_static(bad, 1, p(base), p(base + 4096), p(base + 8192), 4096, None) == binding.EBADLT
+    big = W.workload(3).table()
+    assert binding.adacomp_workspace_bytes(big) > binding.STATIC_SCRATCH_BYTES
+    rc = L.adacomp_compress_static(binding.layer_array(big), len(big), p(base), p(base + 4096), p(base + 8192), 1 << 30, None)
+    assert rc == binding.ETOOBIG and b"16 MiB" in L.adacomp_strerror(rc)
+    assert L.adacomp_compress_static(t, 1, p(base), p(base + 4096), p(base + 8192), 4096, None) == binding.EHIP
+
+
 def test_no_cpu_fallback(L):
     """Without a GPU the set-up call fails loudly instead of computing anything on the host."""
     import torch
