@@ -6,12 +6,18 @@ adacomp_compress on its own gradient and residue (Algorithm 2 of the AdaComp pap
 adacomp_unpack_accumulate sums all learners' packets into a dense gradient (unpack() of
 Algorithm 1).  Inputs are seeded synthetic gradients already resident in HBM when the clock starts.
 
+Every learner reads a gradient it has not seen before at every timed step (n_learners + steps - 1
+buffers, learner k reads buffer k + t at step t), all generated and uploaded before the clock starts.
+
 Prints ONE JSON line.  `value` = bytes of float32 gradient compressed and unpacked per second
 (n_learners * 4 * n_elems per step).  `roofline` prices the dominant kernel (k_fused, the
 streaming pass of compress) by its algorithmic bytes, 12 per element (read dW, read residue,
 write residue), against the MI355X's 8 TB/s HBM peak, with its duration measured by HIP events
 on the launch stream inside the timed region.  `cpu_baseline` times the CPU oracle, as it stands,
-on a bounded sample of the same workload.  Beside these, never as `value`: `unpack_update` (the
+on a bounded sample of the same workload; `parity_checked` says whether step 0 of the calls that
+were timed gave, bit for bit, the packets, residues and dense sum that oracle run produced (the
+run exits non-zero if not); `per_config` holds the other four configurations, each as configured.
+Beside these, never as `value`: `unpack_update` (the
 fused unpack + average + optimizer step) and `lazy_residue` (the same steps through
 adacomp_compress_batch_lazy, with the residue sync inside its timed region).
 """
@@ -27,6 +33,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+MAX_GRAD_BUFFERS = 96  # gradient buffers held at most (48 GB on the largest workload)
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_fused_hbm_traffic.txt")
 
 
@@ -49,6 +56,65 @@ def measured_traffic(workload_name):
         return None
 
 
+def small_config(wl, dev, threads, L, binding, A, W, torch, ctypes, repeats=5):
+    """One of the smaller configurations exactly as configured: wl.n_learners learners, wl.n_steps
+    steps from zero residues, a fresh gradient per learner and step (n + K - 1 buffers), one
+    adacomp_compress_batch and one adacomp_unpack_accumulate per step.  The whole sequence is run
+    `repeats` times from the same initial state (after one untimed run) and the median is reported."""
+    n, K = wl.n_learners, wl.n_steps
+    table, n_total, n_params = wl.table(), wl.n_total, wl.n_params
+    grads = [torch.from_numpy(W.gradient(wl, i, 0, seed=0, threads=threads)).to(dev) for i in range(n + K - 1)]
+    ws = torch.zeros(A.adacomp_workspace_bytes_batch(table, n), dtype=torch.uint8, device=dev)
+    A.adacomp_workspace_init(table, ws)
+    bound = A.adacomp_packet_bound(table)
+    residue = [torch.zeros(n_total, dtype=torch.float32, device=dev) for _ in range(n)]
+    packets = [torch.zeros(bound, dtype=torch.uint8, device=dev) for _ in range(n)]
+    dense = torch.zeros(n_total, dtype=torch.float32, device=dev)
+    vp = ctypes.c_void_p
+    layers_c = binding.layer_array(table)
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    ws_p, ws_n = vp(ws.data_ptr()), ws.numel()
+    pk_ptrs = (vp * n)(*[p.data_ptr() for p in packets])
+    res_ptrs = (vp * n)(*[r.data_ptr() for r in residue])
+    grad_ptrs = [(vp * n)(*[grads[k + t].data_ptr() for k in range(n)]) for t in range(K)]
+    dense_p = vp(dense.data_ptr())
+    times = []
+    try:
+        for rep in range(repeats + 1):
+            for r in residue:
+                r.zero_()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(K):
+                rc = L.adacomp_compress_batch(layers_c, len(table), n, grad_ptrs[t], res_ptrs, pk_ptrs, bound, ws_p, ws_n, stream)
+                if rc:
+                    raise RuntimeError(f"adacomp_compress_batch: {rc}")
+                rc = L.adacomp_unpack_accumulate(layers_c, len(table), pk_ptrs, n, dense_p, ws_p, ws_n, stream)
+                if rc:
+                    raise RuntimeError(f"adacomp_unpack_accumulate: {rc}")
+            torch.cuda.synchronize()
+            if rep:
+                times.append((time.perf_counter() - t0) * 1e3 / K)
+        times.sort()
+        ms = times[len(times) // 2]
+        n_sel = total_bytes = paper_bits = 0
+        for p in packets:   # the last step's packets
+            head, recs = A.read_packet_summary(p)
+            n_sel += int(head["n_selected"])
+            total_bytes += int(head["total_bytes"])
+            paper_bits += int(sum(int(r["word_bits"]) * int(r["n_selected"]) for r in recs))
+        pbar = total_bytes / n
+        step_alg = n * (12 * n_params + pbar) + 4 * n_params + n * pbar
+        return {"configuration": wl.index, "n_learners": n, "steps": K, "n_elems": n_params,
+                "ms_per_step": round(ms, 4), "value": round(n * 4 * n_params / (ms * 1e-3) / 1e9, 2), "unit": "GB/s",
+                "hbm_frac_step_algorithmic": round(step_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "compression_last_step": {"paper_accounting": round(32.0 * n_params * n / max(1, paper_bits), 2),
+                                          "wire": round(4.0 * n_params * n / max(1, total_bytes), 2)},
+                "timing": f"median of {repeats} runs of all {K} steps from zero residues, host clock around the run"}
+    finally:
+        A.adacomp_workspace_release(ws)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +125,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket k_fused with HIP events")
     ap.add_argument("--no-lazy-leg", action="store_true", help="skip the extra leg through adacomp_compress_batch_lazy")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the per_config leg (configurations 1-4 as configured)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one step captured in a HIP graph (for the small, launch-bound workloads; "
                          "no roofline object, since events cannot be read back from a graph)")
@@ -89,14 +156,18 @@ def main():
     args.no_batch = args.batch == "off"
     threads = min(16, os.cpu_count() or 1)
 
-    # ---- inputs: one seeded gradient buffer per learner; learner k uses buffer (k + t) mod n at
-    #      step t, so every learner sees a fresh draw each step and a step never uses a buffer twice
+    # ---- inputs: a fresh seeded draw for every (learner, step): n_learners + K - 1 gradient buffers,
+    #      learner k reads buffer k + t at step t, so within the timed region no learner ever sees a
+    #      gradient twice and no step uses a buffer twice.  All of it is generated and uploaded
+    #      before the clock starts.  (Very long runs wrap around after MAX_GRAD_BUFFERS; the line says so.)
     t0 = time.time()
+    n_buf = min(n_learners + max(K, Wm, 1) - 1, max(n_learners, MAX_GRAD_BUFFERS))
     grads = []
-    for i in range(n_learners):
+    for i in range(n_buf):
         g = W.gradient(wl, i, 0, seed=0, threads=threads)
         grads.append(torch.from_numpy(g).to(dev))
-    log(f"{wl.name}: {n_params} elements x {n_learners} learners generated and uploaded in {time.time() - t0:.1f}s")
+    fresh = n_buf >= n_learners + K - 1
+    log(f"{wl.name}: {n_params} elements x {n_buf} gradient buffers ({n_learners} learners, {K} steps) generated and uploaded in {time.time() - t0:.1f}s")
 
     ws = torch.zeros(A.adacomp_workspace_bytes_batch(table, n_learners), dtype=torch.uint8, device=dev)
     A.adacomp_workspace_init(table, ws)
@@ -116,21 +187,21 @@ def main():
 
     vp = ctypes.c_void_p
     res_ptrs = (vp * n_learners)(*[r.data_ptr() for r in residue])
-    grad_ptrs = [(vp * n_learners)(*[grads[(k + t) % n_learners].data_ptr() for k in range(n_learners)])
-                 for t in range(n_learners)]
+    n_sets = n_buf - n_learners + 1   # gradient sets: set t holds the buffers of step t
+    grad_ptrs = [(vp * n_learners)(*[grads[k + t].data_ptr() for k in range(n_learners)]) for t in range(n_sets)]
 
     cur = {"stream": stream}   # the stream the calls go to: torch's current one, or the capture stream
 
     def compress_all(t):
         stream = cur["stream"]
         if not args.no_batch:
-            rc = L.adacomp_compress_batch(layers_c, len(table), n_learners, grad_ptrs[t % n_learners], res_ptrs,
+            rc = L.adacomp_compress_batch(layers_c, len(table), n_learners, grad_ptrs[t % n_sets], res_ptrs,
                                           pk_ptrs, bound, ws_p, ws_n, stream)
             if rc:
                 raise RuntimeError(f"adacomp_compress_batch: {rc}")
             return
         for k in range(n_learners):
-            rc = L.adacomp_compress(layers_c, len(table), ctypes.c_void_p(grads[(k + t) % n_learners].data_ptr()),
+            rc = L.adacomp_compress(layers_c, len(table), ctypes.c_void_p(grads[k + t % n_sets].data_ptr()),
                                     ctypes.c_void_p(residue[k].data_ptr()), ctypes.c_void_p(packets[k].data_ptr()),
                                     bound, ws_p, ws_n, stream)
             if rc:
@@ -234,6 +305,7 @@ def main():
         roofline = {"bound": "hbm", "kernel": "k_fused", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": (measured_traffic(wl.name) or 0) * per_launch or None,
+                    "traffic_source": "committed rocprofv3 --pmc summary profiles/k_fused_hbm_traffic.txt (not a counter of this run)",
                     "algorithmic_bytes_per_launch": alg_bytes_launch, "learners_per_launch": per_launch,
                     "avg_launch_ms": round(dur_ms, 5), "launches": int(fused_n)}
     # whole step by algorithmic bytes: n * (12 N + P) + 4 N + n * P
@@ -282,7 +354,7 @@ def main():
         t1 = time.perf_counter()
         for t in range(K):   # the same three event records per step as the eager loop above
             lev[t][0].record()
-            rc = L.adacomp_compress_batch_lazy(layers_c, len(table), n_learners, grad_ptrs[t % n_learners], res_ptrs,
+            rc = L.adacomp_compress_batch_lazy(layers_c, len(table), n_learners, grad_ptrs[t % n_sets], res_ptrs,
                                                pk_ptrs, bound, ws_p, ws_n, stream)
             if rc:
                 raise RuntimeError(f"adacomp_compress_batch_lazy: {rc}")
@@ -308,6 +380,7 @@ def main():
 
     # ---- CPU oracle on a bounded sample ----------------------------------------------------------------
     cpu = None
+    parity = None
     if not args.no_cpu_baseline:
         import oracle
         orc = oracle.Oracle()
@@ -339,7 +412,45 @@ def main():
         dt_all = time.perf_counter() - t1
         cpu["all_cores"] = {"value": round(n_learners * 4 * n_params / dt_all / 1e9, 4), "unit": "GB/s", "cores": n_thr,
                             "sample": f"{n_learners} learner(s) x 1 step, one learner per thread, then one unpack, {dt_all:.1f}s"}
-        del hosts, pk
+        # ---- the run checks itself: step 0 from zero residues through the calls that were timed, every
+        #      packet, every residue and the dense sum against what the oracle has just computed -------
+        sum_want = orc.unpack_accumulate(table, pk, n_total)
+        for r in residue:
+            r.zero_()
+        compress_all(0)
+        unpack_all()
+        torch.cuda.synchronize()
+        mask = np.zeros(n_total, bool)
+        for off, n, _ in table:
+            mask[off:off + n] = True
+        bad = []
+        for k in range(n_learners):
+            got = packets[k][:pk[k].size].cpu().numpy()
+            if not np.array_equal(got, pk[k]):
+                bad.append(f"packet {k}")
+            if not np.array_equal(residue[k].cpu().numpy()[mask].view(np.uint32), hosts[k][1][mask].view(np.uint32)):
+                bad.append(f"residue {k}")
+        if not np.array_equal(dense.cpu().numpy()[mask].view(np.uint32), sum_want[mask].view(np.uint32)):
+            bad.append("dense sum")
+        parity = {"against": "oracle", "step": 0, "packets": n_learners, "residues": n_learners, "dense_sum": True,
+                  "bit_equal": not bad}
+        if bad:
+            log("PARITY FAILURE against the oracle: " + ", ".join(bad))
+        del hosts, pk, sum_want
+
+    # ---- the other four configurations, each as configured (its learners, its number of steps, from
+    #      zero residues, one batched compress call and one unpack per step) ---------------------------
+    per_config = None
+    if args.workload == 5 and not args.no_per_config and not args.graph and not args.no_batch:
+        A.adacomp_workspace_release(ws)
+        del grads, residue, packets, dense, ws
+        torch.cuda.empty_cache()
+        per_config = {}
+        for idx in (1, 2, 3, 4):
+            try:
+                per_config[W.workload(idx).name] = small_config(W.workload(idx), dev, threads, L, binding, A, W, torch, ctypes)
+            except Exception as e:  # the main line must not depend on this leg
+                per_config[W.workload(idx).name] = {"error": str(e)}
 
     out = {
         "metric": "GB/s gradient compressed+unpacked", "value": round(value, 2), "unit": "GB/s",
@@ -348,10 +459,13 @@ def main():
         "config": {"workload": f"{wl.name} (configuration {wl.index}): {len(table)} layers, {n_params} fp32 elements, "
                                f"L_T {sorted(set(l[2] for l in table))}, {n_learners} simulated learners, residues start at zero",
                    "n_learners": n_learners, "n_elems": n_params, "dist": wl.dist, "seed": 0,
+                   "gradient_buffers": n_buf, "fresh_gradient_per_learner_and_step": fresh,
                    "compress_call": "adacomp_compress" if args.no_batch else "adacomp_compress_batch",
                    "launch": "hip_graph_replay" if args.graph else "direct"},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "parity_checked": parity,
+        "per_config": per_config,
         "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),
         "compress_ms_per_step": None if graph is not None else round(compress_ms, 4),
         "unpack_ms_per_step": None if graph is not None else round(unpack_ms, 4),
@@ -363,6 +477,8 @@ def main():
                         "paper_context": "~40x conv / ~200x FC-LSTM on trained gradients"},
     }
     print(json.dumps(out), flush=True)
+    if parity is not None and not parity["bit_equal"]:
+        sys.exit("bench.py: the timed path's output differs from the oracle's (see parity_checked)")
 
 
 if __name__ == "__main__":
