@@ -110,21 +110,28 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         ld.n_ctiles = nt;
         p.n_class_tiles[cls] += nt;
         if (T <= 64u) p.has_short_bins = true;
+        // The staging array is indexed by position in the tile table, not by address: a tile's stretch
+        // starts where the stretches of the tiles before it end (each rounded up to 4 entries, which keeps
+        // every stretch 8-byte aligned), so its size follows the element count whatever holes the table has.
+        const uint64_t full_tile = uint64_t(bpt) * T, full_stretch = (full_tile + 3u) & ~uint64_t(3);
         if (tables) {
             for (uint32_t t = 0; t < nt; ++t) {
                 TileDev td;
                 const uint32_t first_bin = t * bpt;
                 const uint64_t e0 = uint64_t(first_bin) * T;
                 td.elem_base = layers[l].elem_offset + e0;
-                td.n_elems = uint32_t(std::min<uint64_t>(uint64_t(bpt) * T, n - e0));
+                td.stage_base = uint32_t(p.stage_entries + full_stretch * t);
+                td.n_elems = uint16_t(std::min<uint64_t>(full_tile, n - e0));
                 td.L_T = T;
                 td.magic = bin_magic(T);
-                td.n_bins = (td.n_elems + T - 1) / T;
+                td.n_bins = uint16_t((uint32_t(td.n_elems) + T - 1) / T);
                 td.first_bin = first_bin;
                 td.layer_flags = l | (uint32_t(cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
                 p.ctiles.push_back(td);
             }
         }
+        p.stage_entries += full_stretch * (nt - 1) + ((n - full_tile * (nt - 1) + 3u) & ~uint64_t(3));
+        if (p.stage_entries >= (uint64_t(1) << 32)) return ADACOMP_EINVAL;
         n_ctiles += nt;
 
         // ---- unpack tiles: a power-of-two number of bins inside one 64-bin chunk, or slices of
@@ -245,7 +252,7 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
     w.gmax = off;        off = pad256(off + 4 * size_t(p.n_bins_total));
     w.chunk_rel = off;   off = pad256(off + 4 * size_t(p.n_chunks_total));
     if (off >= (size_t(1) << 32)) return ADACOMP_EINVAL;
-    w.stage = off;       off = pad256(off + 2 * size_t(p.elem_span) + 128);  // slack: k_place reads up to 64 entries from a tile's start
+    w.stage = off;       off = pad256(off + 2 * size_t(p.stage_entries) + 128);  // slack: k_place reads up to 64 entries from a tile's start
     w.scratch_stride = off;
     return ADACOMP_OK;
 }
@@ -288,7 +295,7 @@ int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *work
     // copy the scalars only; the tables already live on the device
     out.n_layers = p.n_layers; out.n_ctiles = p.n_ctiles; out.n_utiles = p.n_utiles; out.n_ugroups = p.n_ugroups; out.n_ugroups8 = p.n_ugroups8; out.n_usingles8 = p.n_usingles8;
     out.n_bins_total = p.n_bins_total; out.n_chunks_total = p.n_chunks_total;
-    out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total;
+    out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total; out.stage_entries = p.stage_entries;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
     for (int c = 0; c < 2; ++c) out.n_class_tiles[c] = p.n_class_tiles[c];
     out.has_short_bins = p.has_short_bins;

@@ -178,8 +178,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
         for (uint32_t i = tid; i < uint32_t(J) * WG / 4u; i += WG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
         // four entries per load: a tile's stretch of the staging area starts on an 8-byte boundary
-        // (tiles start at multiples of 4 elements) and what lies behind its last entry is readable
-        const uint2 *prev_stage = reinterpret_cast<const uint2 *>(stage_all + td.elem_base);
+        // (stretches are multiples of 4 entries) and what lies behind its last entry is readable
+        const uint2 *prev_stage = reinterpret_cast<const uint2 *>(stage_all + td.stage_base);
         const uint32_t prev_n = prev_count < n ? prev_count : n;
         for (uint32_t q = tid; 4u * q < prev_n; q += WG) {
             const uint2 v = prev_stage[q];
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     const uint32_t tile_total = __shfl(row_incl, WAVES * J - 1, 64);
 
     // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
-    uint16_t *__restrict__ stage = stage_all + td.elem_base;
+    uint16_t *__restrict__ stage = stage_all + td.stage_base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     const TileOut to = tile_out[tile];
     const uint32_t cnt = to.count;
     const uint32_t base = FOLD ? s_excl[tile] - s_excl[a.layers[l].ctile_start] : to.base;
-    const uint16_t *__restrict__ stage = stage_all + td.elem_base;
+    const uint16_t *__restrict__ stage = stage_all + td.stage_base;
     float *__restrict__ rs = a.residue[lr] + td.elem_base;
     const uint32_t s_first = stage[sub];  // speculative: the staging array has 64 entries of slack
     const float scale = FOLD ? fold_layer_scale(tile_out, a.layers[l].ctile_start, a.layers[l].n_ctiles, a.layers[l].n_bins, sub)

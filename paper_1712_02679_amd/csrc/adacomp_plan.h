@@ -36,10 +36,12 @@ static_assert(sizeof(LayerDev) == 64, "LayerDev layout");
 // One workgroup's share of adacomp_compress: whole bins of one layer (32 bytes).
 struct TileDev {
     uint64_t elem_base;   // first element in grad / residue (layer offset included)
-    uint32_t n_elems;     // elements in the tile, <= 4096 or 16384 by register class
+    uint32_t stage_base;  // first entry of the tile's stretch of the staging array: the tiles' element counts,
+                          // each rounded up to 4, summed over the tiles before it (so a multiple of 4)
     uint32_t L_T;
     uint32_t magic;       // floor(2^32 / L_T) + 1: bin = umulhi(e, magic) for e < 16384 (L_T > 1)
-    uint32_t n_bins;      // bins in the tile, <= kMaxTileBins
+    uint16_t n_elems;     // elements in the tile, <= 4096 or 16384 by register class
+    uint16_t n_bins;      // bins in the tile, <= kMaxTileBins
     uint32_t first_bin;   // index of the tile's first bin inside the layer
     uint32_t layer_flags; // bits 0..23 layer, bit 24 register class (0: 4096-element tiles, 1: 16384), bit 31 aligned
     __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
@@ -93,7 +95,7 @@ struct WorkspaceLayout {
     size_t tile_out = 0;                                // TileOut per compress tile
     size_t layer_nsel = 0, layer_scale = 0;             // per layer
     size_t gmax = 0, chunk_rel = 0;                     // per bin / per chunk
-    size_t stage = 0;                                   // uint16 per element: words before placement
+    size_t stage = 0;                                   // uint16 per element of the layers (not of the address span): words before placement
     size_t total(size_t n_learners) const { return scratch + scratch_stride * n_learners; }
 };
 
@@ -104,6 +106,7 @@ struct Plan {
     uint32_t n_bins_total = 0, n_chunks_total = 0;
     uint64_t elem_span = 0;     // max over layers of elem_offset + n_elems
     uint64_t n_elems_total = 0;
+    uint64_t stage_entries = 0; // entries of the staging array: sum over the compress tiles of their element counts rounded up to 4
     uint64_t fixed_bytes = 0;   // packet bytes before the first word
     uint64_t bound_bytes = 0;   // packet bytes with every element sent
     uint32_t n_class_tiles[2] = {0, 0};  // compress tiles of 4096 / of 16384 elements

@@ -25,6 +25,7 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
         return 101;
     // compress tiles: whole bins, in order, covering each layer exactly; sizes fit the register class
     uint32_t ct = 0;
+    uint64_t stage_next = 0;   // stretches of the staging array: one after the other in tile order, each a multiple of 4 entries
     for (uint32_t l = 0; l < p.n_layers; ++l) {
         const LayerDev &ld = p.layers[l];
         if (ld.ctile_start != ct) return 102;
@@ -39,6 +40,9 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
             if (td.aligned() != (td.elem_base % 4 == 0)) return 106;
             if (td.magic != bin_magic(td.L_T)) return 107;
             if (td.n_elems > 16384u) return 108;  // the multiply-shift bin index is checked below this
+            if (td.stage_base % 4u != 0 || td.stage_base < stage_next) return 117;   // stretches do not overlap
+            stage_next = uint64_t(td.stage_base) + td.n_elems;
+            if (stage_next > p.stage_entries) return 118;
             e += td.n_elems;
             bin += td.n_bins;
             if (i + 1 < ld.n_ctiles && td.n_elems % td.L_T != 0) return 109;  // only the last tile may end in a short bin
@@ -110,7 +114,8 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
     if (w.cclass + 4 * size_t(p.n_ctiles) > w.utiles) return 144;
     if (!(w.layers < w.ctiles && w.ctiles <= w.cclass && w.cclass <= w.utiles && w.utiles <= w.ugroups && w.ugroups <= w.usingles && w.usingles <= w.scratch)) return 140;
     if (w.usingles + sizeof(UGroupDev) * size_t(p.n_utiles) > w.scratch) return 141;
-    if (w.stage + 2 * size_t(p.elem_span) + 128 > w.scratch_stride) return 142;  // k_place reads 64 entries from a tile's start
+    if (w.stage + 2 * size_t(p.stage_entries) + 128 > w.scratch_stride) return 142;  // k_place reads 64 entries from a tile's start
+    if (p.stage_entries > p.n_elems_total + 3ull * p.n_ctiles) return 145;       // the array follows the element count, not the address span
     if (w.total(3) != adacomp_workspace_bytes_batch(t.data(), uint32_t(t.size()), 3)) return 143;
     g_tiles_checked += p.n_ctiles + p.n_utiles;
     g_groups_checked += p.n_ugroups;

@@ -56,6 +56,18 @@ def test_sizes_follow_the_container_layout(L):
         assert ws > 2 * W.workload(i).n_total and ws < 2.5 * W.workload(i).n_total + (1 << 20)
 
 
+def test_workspace_follows_the_element_count_not_the_address_span(L):
+    far = [(4096, 50 * 4000 + 7, 50), (2 ** 32 + 4096, 500 * 600 + 13, 500), (2 ** 32 + 2 ** 31, 16384 * 6 + 5, 16384)]
+    n_params = sum(n for _, n, _ in far)
+    near = []
+    off = 0
+    for _, n, T in far:
+        near.append((off, n, T))
+        off += (n + 3) // 4 * 4
+    assert binding.adacomp_workspace_bytes(far) == binding.adacomp_workspace_bytes(near) <= 3 * n_params
+    assert binding.adacomp_workspace_bytes_batch(far, 4) - binding.adacomp_workspace_bytes_batch(far, 3) <= 2.2 * n_params
+
+
 def test_bad_tables_are_refused(L):
     assert binding.adacomp_packet_bound([(0, 0, 50)]) == 0           # empty layer
     assert binding.adacomp_packet_bound([(0, 10, 0)]) == 0           # L_T = 0

@@ -101,6 +101,8 @@ def test_layers_beyond_2_to_32_elements(H, oracle_lib):
                                  ("c", 16384 * 6 + 5, 16384, 2 ** 32 + 2 ** 31)], dist="normal_outliers")
     table, n_total = wl.table(), wl.n_total
     assert n_total > 2 ** 32 + 2 ** 31
+    # the workspace follows the number of elements in the layers, not the span of addresses they cover
+    assert A.adacomp_workspace_bytes(table) <= 3 * wl.n_params
     windows = [(max(0, off - 1024), min(n_total, off + n + 1024)) for off, n, _ in table]
     gpu = G.GpuSide(table, n_total, 2, batch=True)
     try:
