@@ -73,8 +73,9 @@ extern "C" {
 #define ADACOMP_STATUS_COMPLETE 0u
 #define ADACOMP_STATUS_TRUNCATED 1u /* capacity was too small: words beyond it were not written */
 
-/* One layer of the flat gradient ("AdaComp is applied to every layer separately"; L_T is the
- * paper's one hyper-parameter, per layer type: 50 for convolutions, 500 for FC / LSTM). */
+/* One layer of the flat gradient: the method treats every layer on its own (section "Adaptive
+ * Residual Gradient Compression (AdaComp) Technique"); L_T is its one hyper-parameter, chosen per
+ * layer type: 50 for convolutions, 500 for FC / LSTM (Table 2). */
 typedef struct {
     uint64_t elem_offset; /* first element in grad / residue / dense_out; multiple of 4        */
     uint64_t n_elems;     /* 1 .. 2^31-1; need not be a multiple of L_T (the last bin is short) */
@@ -179,8 +180,8 @@ int adacomp_compress_batch(const adacomp_layer_t *layers, uint32_t n_layers, uin
                            size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* pack() with another selection rule or soft-threshold factor: the mechanisms of the paper's
- * ablations (section "Robustness of the AdaComp Technique": Local Selection = "similar to AdaComp's
- * local selection scheme, but without applying a soft-threshold"; section "Adaptive Residual
+ * ablations (section "Robustness of the AdaComp Technique": Local Selection keeps the selection
+ * inside bins and leaves the soft threshold out, so only bin maxima go; section "Adaptive Residual
  * Gradient Compression (AdaComp) Technique": factors 1.5 - 3.0 were studied, 2 chosen so that only
  * additions are needed).  Everything else (bins, g_max, scale, quantiser, residue, packet) is as
  * in adacomp_compress_batch, which is this call with ADACOMP_RULE_ADACOMP and factor 2.
@@ -199,8 +200,8 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
                              size_t packet_capacity, uint32_t rule, float soft_factor, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
-/* pack() with the residue corrections deferred.  The last step of Algorithm 2, residue(index) <-
- * G(index) - Gq(index) at the sent elements, is a scattered read-modify-write that costs about 6 %
+/* pack() with the residue corrections deferred.  The last step of Algorithm 2, the subtraction of
+ * the quantised value from G at the sent elements, is a scattered read-modify-write that costs about 6 %
  * of the whole pack() on a large fully connected table; nothing needs its result before the same
  * learner's next pack(), which reads the whole residue anyway.  This call sends exactly the
  * packets adacomp_compress_batch sends, but leaves the corrections in the workspace and applies
@@ -215,7 +216,8 @@ int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, u
  *   - The host keeps the books when a call is enqueued: use one stream per workspace.  A HIP graph
  *     holds the kernels of the call as it was captured: capture a lazy call while corrections
  *     wait (after a first lazy call outside the capture) and replay it only in that state.
- * After the sync the residues are bit for bit those of the eager calls. */
+ * After the sync the residues are bit for bit those of the eager calls.  If a launch of this call
+ * fails (ADACOMP_EHIP) the residues are unspecified and nothing is left waiting. */
 int adacomp_compress_batch_lazy(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
                                 const float *const *grads, float *const *residues, void *const *packets_out,
                                 size_t packet_capacity, void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -258,8 +260,8 @@ typedef struct {
     float bias1, bias2; /* Adam's 1 - beta1^t and 1 - beta2^t for this step, computed by the caller */
 } adacomp_optimizer_t;
 
-/* Like adacomp_unpack_accumulate, then g = sum / n_learners ("Average among all learners") and one
- * optimizer step on the weights ("Performed locally at each learner"), without writing the dense
+/* Like adacomp_unpack_accumulate, then g = sum / n_learners (averageGradients() of Algorithm 1) and
+ * one optimizer step on the weights (updateWeights(), which every learner does for itself), without writing the dense
  * gradient to memory and reading it back.  The paper trains with SGD with momentum 0.9 and with
  * Adam (sections "Experiment Results", "Robustness of the AdaComp Technique") and leaves the
  * update rule to the framework; the forms above are the usual ones, each arithmetic operation a
@@ -273,50 +275,12 @@ int adacomp_unpack_update(const adacomp_layer_t *layers, uint32_t n_layers, cons
                           uint32_t n_learners, float *dense_out, float *weights, float *state1, float *state2,
                           const adacomp_optimizer_t *opt, void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* ---- diagnostics ---------------------------------------------------------------------------- */
+/* ---- errors as text ------------------------------------------------------------------------ */
 
 const char *adacomp_strerror(int code);
 
-/* The g_max vector (one float per bin, layers in table order, bins in order) is not needed once
- * the layer scale is known, so compress does not store it unless adacomp_debug_keep_gmax(1) has
- * been called.  adacomp_workspace_gmax says where it is then left inside the workspace: byte
- * offset and number of floats for the first learner of a call, and (if not NULL) the distance in
- * bytes to the next learner's vector in a batched call.  For tests of the first loop of
- * Algorithm 2. */
-int adacomp_debug_keep_gmax(int enable);
-int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, size_t *byte_offset,
-                           size_t *n_bins_total, size_t *learner_stride);
-
-/* Plain float4 device copy of n floats (dst, src 16-byte aligned): the reference kernel against
- * which HBM byte counters and the achievable copy bandwidth are calibrated. */
-int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
-
-/* Host-only exhaustive check of the multiply-shift constants the kernels use to turn an element
- * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
-int adacomp_selftest_binindex(void);
-
-/* Tuning knob of adacomp_unpack_accumulate / adacomp_unpack_update, read by adacomp_workspace_init.
- * A workgroup of the unpack kernel serves a run of up to 8 neighbouring output tiles (4096 elements
- * each) that share their per-bin bookkeeping; the run length is halved until at least n_groups
- * workgroups remain, so that small tables still fill the GPU.  Results do not depend on it.
- * 0 restores the default (2048).  Process-wide; not synchronised with calls on other threads.
- * Returns ADACOMP_OK. */
-int adacomp_tuning_unpack_min_groups(uint32_t n_groups);
-
-/* Tuning knob of the compress calls, read at every call.  Tables of up to 512 compress tiles and
- * 16 layers skip the separate scan launch (layer scales, word offsets): the placement kernel works
- * them out itself.  enable = 0 makes such tables take the three-launch path of the large ones;
- * non-zero restores the default.  Results do not depend on it.  Process-wide; not synchronised with
- * calls on other threads.  Returns ADACOMP_OK. */
-int adacomp_tuning_fold_scan(int enable);
-
-/* Per-kernel timing of the streaming kernel (k_fused) of adacomp_compress / adacomp_compress_batch
- * with HIP events on the caller's stream.  enable = k > 0 starts recording every k-th launch (and
- * clears earlier records; an event pair costs a few microseconds between back-to-back launches, so
- * a timed run samples); 0 stops.  adacomp_timing_read synchronises the recorded events and returns their
- * summed duration, the number of launches and the number of learners those launches covered. */
-int adacomp_timing_enable(int enable);
-int adacomp_timing_read(double *total_ms, uint64_t *n_launches, uint64_t *n_learners);
+/* Diagnostics, tuning knobs and kernel timing are declared in adacomp_debug.h; they are not part of
+ * the stable contract. */
 
 #ifdef __cplusplus
 }

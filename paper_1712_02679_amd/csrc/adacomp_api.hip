@@ -3,11 +3,13 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <unordered_map>
 
+#include "adacomp_debug.h"
 #include "adacomp_plan.h"
 
 namespace adacomp {
@@ -50,8 +52,10 @@ static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
     return ADACOMP_OK;
 }
 
-static uint32_t g_unpack_min_groups = kUnpackMinGroups;
-static bool g_fold_scan = true;
+// process-wide tuning and diagnostic flags (adacomp_debug.h): atomics, so that a compute call on one
+// thread reads a whole value while another thread sets it; no ordering beyond that is promised
+static std::atomic<uint32_t> g_unpack_min_groups{kUnpackMinGroups};
+static std::atomic<bool> g_fold_scan{true};
 
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &p)
 {
@@ -196,7 +200,8 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         //      kUnpackTaperTiles tiles go alone, twice as many before them in pairs, ...): the
         //      launch then ends with short workgroups instead of a few long stragglers. -----------
         uint32_t run = kUnpackGroupTiles;
-        while (run > 1u && n_utiles / run < g_unpack_min_groups) run /= 2u;
+        const uint32_t min_groups = g_unpack_min_groups.load(std::memory_order_relaxed);
+        while (run > 1u && n_utiles / run < min_groups) run /= 2u;
         const uint32_t taper = kUnpackTaperTiles;
         const uint32_t run_max = run;
         for (uint32_t i = 0; i < p.n_utiles; ++i) {
@@ -322,8 +327,10 @@ void register_workspace(const adacomp_layer_t *layers, uint32_t n_layers, const 
 }
 
 // ---- optional event timing of the streaming kernel ---------------------------------------------
+// The records are guarded by g_timing_mu; `on` alone is read without it, so that calls pay nothing
+// while timing is off.
 struct Timing {
-    bool on = false;
+    std::atomic<bool> on{false};
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
     size_t used = 0;
     uint64_t learners = 0;  // learners covered by the recorded launches
@@ -331,7 +338,8 @@ struct Timing {
     uint64_t seen = 0;      // launches since recording started
 };
 static Timing g_timing;
-static bool g_keep_gmax = false;
+static std::mutex g_timing_mu;
+static std::atomic<bool> g_keep_gmax{false};
 
 }  // namespace adacomp
 
@@ -419,7 +427,7 @@ static uint32_t place_lanes_for(const Plan &p)
 // Small tables: no k_scan launch, the placement kernel does the scan itself (see k_place).
 static bool fold_scan_for(const Plan &p)
 {
-    return g_fold_scan && place_lanes_for(p) == 64u && p.n_ctiles <= kFoldTiles && p.n_layers <= kFoldLayers;
+    return g_fold_scan.load(std::memory_order_relaxed) && place_lanes_for(p) == 64u && p.n_ctiles <= kFoldTiles && p.n_layers <= kFoldLayers;
 }
 
 static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
@@ -470,7 +478,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.o_chunk_rel = uint32_t(p.ws.chunk_rel); a.o_stage = p.ws.stage;
     a.n_tiles = p.n_ctiles;
     a.n_layers = p.n_layers;
-    a.keep_gmax = g_keep_gmax ? 1u : 0u;
+    a.keep_gmax = g_keep_gmax.load(std::memory_order_relaxed) ? 1u : 0u;
     a.class_tiles = (p.n_class_tiles[0] && p.n_class_tiles[1]) ? reinterpret_cast<const uint32_t *>(ws + p.ws.cclass) : nullptr;
     a.place_lanes = place_lanes_for(p);
     a.fold_scan = fold_scan_for(p) ? 1u : 0u;
@@ -487,6 +495,8 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     // more before its first store and loses more at every launch boundary: two learners per launch
     // (or four) are 1.5 % faster per step there, and 0.3 % (1 %) slower on the eager path.
     const uint32_t per_launch_max = p.n_elems_total >= kSplitElems ? (lazy ? 2u : 1u) : kMaxBatch;
+    auto enqueue = [&]() -> int {
+    int rc = ADACOMP_OK;
     for (uint32_t done = 0; done < n_learners; done += kMaxBatch) {
         const uint32_t now = std::min(n_learners - done, kMaxBatch);
         a.n_learners = now;
@@ -499,16 +509,20 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
         for (uint32_t f = 0; f < now; f += per_launch_max) {
             a.fused_first = f;
             a.fused_count = std::min(per_launch_max, now - f);
-            std::pair<hipEvent_t, hipEvent_t> *ev = nullptr;
-            if (g_timing.on && (g_timing.seen++ % g_timing.stride) == 0) {
-                if (g_timing.used == g_timing.pool.size()) {
-                    hipEvent_t e0, e1;
-                    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
-                    g_timing.pool.emplace_back(e0, e1);
+            hipEvent_t ev_end = nullptr;   // set: this launch is bracketed by an event pair
+            if (g_timing.on.load(std::memory_order_relaxed)) {
+                std::lock_guard<std::mutex> lk(g_timing_mu);
+                if (g_timing.on.load(std::memory_order_relaxed) && (g_timing.seen++ % g_timing.stride) == 0) {
+                    if (g_timing.used == g_timing.pool.size()) {
+                        hipEvent_t e0, e1;
+                        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ADACOMP_EHIP;
+                        g_timing.pool.emplace_back(e0, e1);
+                    }
+                    const std::pair<hipEvent_t, hipEvent_t> &ev = g_timing.pool[g_timing.used++];
+                    g_timing.learners += a.fused_count;
+                    if (hipEventRecord(ev.first, s) != hipSuccess) return ADACOMP_EHIP;
+                    ev_end = ev.second;   // the handle itself: the pool may grow under another thread
                 }
-                ev = &g_timing.pool[g_timing.used++];
-                g_timing.learners += a.fused_count;
-                if (hipEventRecord(ev->first, s) != hipSuccess) return ADACOMP_EHIP;
             }
             for (int c = 0; c < 2; ++c) {
                 if (p.n_class_tiles[c] == 0) continue;
@@ -516,17 +530,26 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
                 a.class_count = p.n_class_tiles[c];
                 if ((rc = launch_fused(a, c, hip_stream)) != ADACOMP_OK) return rc;
             }
-            if (ev && hipEventRecord(ev->second, s) != hipSuccess) return ADACOMP_EHIP;
+            if (ev_end && hipEventRecord(ev_end, s) != hipSuccess) return ADACOMP_EHIP;
         }
         if (!a.fold_scan && (rc = launch_scan(a, hip_stream)) != ADACOMP_OK) return rc;
         if ((rc = launch_place(a, hip_stream)) != ADACOMP_OK) return rc;
     }
-    if (lazy) {
+    return ADACOMP_OK;
+    };
+    rc = enqueue();
+    if (lazy || corrections_wait) {
+        // After a failure part of the way through, some kernels of this call may have applied and
+        // overwritten the corrections that waited while others did not run: nothing can be said to
+        // wait any more, and the residues are unspecified (as after a failed adacomp_residue_sync).
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_ws.find(workspace);
-        if (it != g_ws.end()) it->second.waiting.assign(residues, residues + n_learners);
+        if (it != g_ws.end()) {
+            if (rc == ADACOMP_OK) it->second.waiting.assign(residues, residues + n_learners);
+            else it->second.waiting.clear();
+        }
     }
-    return ADACOMP_OK;
+    return rc;
 }
 
 int adacomp_compress_variant(const adacomp_layer_t *layers, uint32_t n_layers, uint32_t n_learners,
@@ -803,6 +826,7 @@ int adacomp_tuning_unpack_min_groups(uint32_t n_groups)
 
 int adacomp_timing_enable(int enable)
 {
+    std::lock_guard<std::mutex> lk(g_timing_mu);
     g_timing.on = enable != 0;
     g_timing.stride = enable > 0 ? uint32_t(enable) : 1u;
     g_timing.used = 0;
@@ -814,6 +838,7 @@ int adacomp_timing_enable(int enable)
 int adacomp_timing_read(double *total_ms, uint64_t *n_launches, uint64_t *n_learners)
 {
     if (!total_ms || !n_launches || !n_learners) return ADACOMP_EINVAL;
+    std::lock_guard<std::mutex> lk(g_timing_mu);
     double sum = 0.0;
     for (size_t i = 0; i < g_timing.used; ++i) {
         float ms = 0.f;

@@ -314,7 +314,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     const uint32_t row_incl = wave_incl_scan(lane < uint32_t(WAVES * J) ? s_wtot[lane] : 0u);
     const uint32_t tile_total = __shfl(row_incl, WAVES * J - 1, 64);
 
-    // ---- "add Gq(index) to a pack vector": staged as (tile-local index << 2 | code) ------------
+    // ---- the pack vector of Algorithm 2: a sent element is staged as (tile-local index << 2 | code) --
     uint16_t *__restrict__ stage = stage_all + td.stage_base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
@@ -641,7 +641,7 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
             const uint32_t p = p0 + kPlaceLanes * u;
             s[u] = p < cnt ? (p == sub ? s_first : uint32_t(stage[p])) : 0u;  // 0: code 0, never a real entry
         }
-        // residue(index) <- G(index) - Gq(index), Gq = sign(G) * scale; G is what k_fused left in the
+        // The sent elements' residue update of Algorithm 2: G minus sign(G) * scale; G is what k_fused left in the
         // residue: a read-modify-write, measured at a 64-byte read and a 32-byte write per word.
         // (Keeping G next to the staged entry, so that this becomes a plain store, was built and
         // measured three times: in an array of its own for all layers, for short-bin layers only,

@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include "adacomp.h"
+#include "adacomp_debug.h"
 #include "adacomp_plan.h"
 
 // Invariants of the tile tables that the kernels index without further checks: every table is
