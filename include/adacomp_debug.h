@@ -50,6 +50,12 @@ int adacomp_tuning_unpack_min_groups(uint32_t n_groups);
  * calls on other threads.  Returns ADACOMP_OK. */
 int adacomp_tuning_fold_scan(int enable);
 
+/* Tuning knob of the eager compress calls, read at every call.  Large tables with short bins
+ * (some L_T <= 64) correct the residue tile by tile, whole 64-byte lines at a time, in the placement
+ * kernel; enable = 0 makes them take the word-by-word placement of the other tables; non-zero
+ * restores the default.  Results do not depend on it.  Returns ADACOMP_OK. */
+int adacomp_tuning_place_tiled(int enable);
+
 /* Per-kernel timing of the streaming kernel (k_fused) of adacomp_compress / adacomp_compress_batch
  * with HIP events on the caller's stream.  enable = k > 0 starts recording every k-th launch (and
  * clears earlier records; an event pair costs a few microseconds between back-to-back launches, so

@@ -25,7 +25,7 @@ EXPORTS = [
     "adacomp_compress_batch_lazy", "adacomp_residue_sync",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
     "adacomp_copy_f32",
-    "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_tuning_fold_scan", "adacomp_timing_enable", "adacomp_timing_read",
+    "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_tuning_fold_scan", "adacomp_tuning_place_tiled", "adacomp_timing_enable", "adacomp_timing_read",
 ]
 
 PACKET_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("status", "<u4"), ("n_layers", "<u4"),
@@ -96,6 +96,7 @@ def lib():
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
         L.adacomp_tuning_unpack_min_groups.argtypes = [ctypes.c_uint32]
         L.adacomp_tuning_fold_scan.argtypes = [ctypes.c_int]
+        L.adacomp_tuning_place_tiled.argtypes = [ctypes.c_int]
         L.adacomp_timing_enable.argtypes = [ctypes.c_int]
         L.adacomp_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64),
                                           ctypes.POINTER(ctypes.c_uint64)]
@@ -266,6 +267,11 @@ def adacomp_tuning_unpack_min_groups(n_groups: int):
 def adacomp_tuning_fold_scan(enable: bool):
     """False: small tables take the three-launch compress path of the large ones; True: the default."""
     _check(lib().adacomp_tuning_fold_scan(1 if enable else 0))
+
+
+def adacomp_tuning_place_tiled(enable: bool):
+    """False: tables with short bins take the word-by-word placement of the others; True: the default."""
+    _check(lib().adacomp_tuning_place_tiled(1 if enable else 0))
 
 
 def adacomp_timing_enable(every: int):

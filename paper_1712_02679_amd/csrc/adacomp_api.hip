@@ -56,6 +56,7 @@ static int validate(const adacomp_layer_t *layers, uint32_t n_layers)
 // thread reads a whole value while another thread sets it; no ordering beyond that is promised
 static std::atomic<uint32_t> g_unpack_min_groups{kUnpackMinGroups};
 static std::atomic<bool> g_fold_scan{true};
+static std::atomic<bool> g_place_tiled{true};
 
 int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Plan &p)
 {
@@ -482,6 +483,9 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     a.class_tiles = (p.n_class_tiles[0] && p.n_class_tiles[1]) ? reinterpret_cast<const uint32_t *>(ws + p.ws.cclass) : nullptr;
     a.place_lanes = place_lanes_for(p);
     a.fold_scan = fold_scan_for(p) ? 1u : 0u;
+    // tables with short bins send a large share of their elements: the eager placement then corrects
+    // the residue tile by tile, whole lines at a time (k_place_tiled), instead of word by word
+    a.place_tiled = (g_place_tiled.load(std::memory_order_relaxed) && p.has_short_bins && !a.fold_scan && !lazy) ? 1u : 0u;
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;
@@ -815,6 +819,12 @@ int adacomp_debug_keep_gmax(int enable)
 int adacomp_tuning_fold_scan(int enable)
 {
     g_fold_scan = enable != 0;
+    return ADACOMP_OK;
+}
+
+int adacomp_tuning_place_tiled(int enable)
+{
+    g_place_tiled = enable != 0;
     return ADACOMP_OK;
 }
 

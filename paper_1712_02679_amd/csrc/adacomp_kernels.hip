@@ -477,6 +477,85 @@ __device__ __forceinline__ float fold_layer_scale(const TileOut *tile_out, const
     return float(s / double(n_bins));
 }
 
+// Header, layer records and zero padding of one learner's packet, by one workgroup of kWG threads
+// (the extra workgroup of a placement launch): 256 layers at a time, word offsets by a block scan
+// of the padded section sizes (all below 2^32: the packet bound is).  FOLD: the layer totals come
+// from s_excl (words of all tiles before each tile) and the scales are worked out here.
+template <bool FOLD>
+__device__ __forceinline__ void place_header(const CompressArgs &a, uint8_t *const packet, const TileOut *const tile_out,
+                                             uint32_t *const layer_nsel, float *const layer_scale, const uint32_t *const s_excl)
+{
+    const uint32_t tid = threadIdx.x;
+    __shared__ uint32_t s_wtot[4];
+    __shared__ float s_fscale[FOLD ? kFoldLayers : 1u];
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (FOLD) {
+        for (uint32_t l = wave; l < a.n_layers; l += 4u) {
+            const float sc = fold_layer_scale(tile_out, a.layers[l].ctile_start, a.layers[l].n_ctiles, a.layers[l].n_bins, lane);
+            if (lane == 0u) s_fscale[l] = sc;
+        }
+        __syncthreads();
+    }
+    uint64_t carry = a.fixed_bytes, nsel_all = 0;
+    for (uint32_t l0 = 0; l0 < a.n_layers; l0 += kWG) {
+        const uint32_t l = l0 + tid;
+        const bool live = l < a.n_layers;
+        LayerDev ld;
+        uint32_t nsel = 0u, bytes = 0u;
+        float scale = 0.f;
+        if (live) {
+            ld = a.layers[l];
+            if (FOLD) {   // and left in the scratch block for whoever applies the corrections later
+                nsel = s_excl[ld.ctile_start + ld.n_ctiles] - s_excl[ld.ctile_start];
+                scale = s_fscale[l];
+                layer_nsel[l] = nsel;
+                layer_scale[l] = scale;
+            } else {
+                nsel = layer_nsel[l];
+                scale = layer_scale[l];
+            }
+            bytes = uint32_t(pad16_dev(uint64_t(nsel) * ld.word_bytes));
+        }
+        const uint32_t incl = wave_incl_scan(bytes);
+        uint32_t nsum = wave_sum(nsel);
+        __syncthreads();  // previous round's readers of s_wtot are done
+        if (lane == 63) s_wtot[wave] = incl;
+        __syncthreads();
+        uint64_t before = carry;
+        for (uint32_t wv = 0; wv < wave; ++wv) before += s_wtot[wv];
+        const uint64_t woff = before + incl - bytes;
+        carry += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
+        if (live) {
+            adacomp_packet_layer_t rec;
+            rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
+            rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
+            rec.scale = scale;
+            rec.n_selected = nsel;
+            rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
+            reinterpret_cast<adacomp_packet_layer_t *>(packet + sizeof(adacomp_packet_header_t))[l] = rec;
+            for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) packet[b] = 0;
+            const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
+            for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) packet[b] = 0;
+            const uint64_t words_end = woff + uint64_t(nsel) * ld.word_bytes;
+            for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
+                if (b < a.capacity) packet[b] = 0;
+        }
+        // total word count: per-wave sums through the same LDS slots
+        __syncthreads();
+        if (lane == 0) s_wtot[wave] = nsum;
+        __syncthreads();
+        nsel_all += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
+    }
+    if (tid == 0) {
+        adacomp_packet_header_t h;
+        h.magic = ADACOMP_PACKET_MAGIC; h.version = ADACOMP_PACKET_VERSION;
+        h.status = carry > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
+        h.n_layers = a.n_layers; h.total_bytes = carry; h.n_selected = nsel_all;
+        *reinterpret_cast<adacomp_packet_header_t *>(packet) = h;
+    }
+}
+
 template <uint32_t LANES, uint32_t MODE, bool FOLD>
 __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 {
@@ -523,76 +602,7 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
 
     if (MODE == kPlaceResidue && blockIdx.x == gridDim.x - 1) return;
     if (MODE != kPlaceResidue && blockIdx.x == gridDim.x - 1) {
-        // ---- header, layer records, zero padding: 256 layers at a time, word offsets by a block
-        //      scan of the padded section sizes (all below 2^32: the packet bound is) --------------
-        __shared__ uint32_t s_wtot[4];
-        __shared__ float s_fscale[FOLD ? kFoldLayers : 1u];
-        const uint32_t lane = tid & 63u;
-        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-        if (FOLD) {
-            for (uint32_t l = wave; l < a.n_layers; l += 4u) {
-                const float sc = fold_layer_scale(tile_out, a.layers[l].ctile_start, a.layers[l].n_ctiles, a.layers[l].n_bins, lane);
-                if (lane == 0u) s_fscale[l] = sc;
-            }
-            __syncthreads();
-        }
-        uint64_t carry = a.fixed_bytes, nsel_all = 0;
-        for (uint32_t l0 = 0; l0 < a.n_layers; l0 += kWG) {
-            const uint32_t l = l0 + tid;
-            const bool live = l < a.n_layers;
-            LayerDev ld;
-            uint32_t nsel = 0u, bytes = 0u;
-            float scale = 0.f;
-            if (live) {
-                ld = a.layers[l];
-                if (FOLD) {   // and left in the scratch block for whoever applies the corrections later
-                    nsel = s_excl[ld.ctile_start + ld.n_ctiles] - s_excl[ld.ctile_start];
-                    scale = s_fscale[l];
-                    layer_nsel[l] = nsel;
-                    layer_scale[l] = scale;
-                } else {
-                    nsel = layer_nsel[l];
-                    scale = layer_scale[l];
-                }
-                bytes = uint32_t(pad16_dev(uint64_t(nsel) * ld.word_bytes));
-            }
-            const uint32_t incl = wave_incl_scan(bytes);
-            uint32_t nsum = wave_sum(nsel);
-            __syncthreads();  // previous round's readers of s_wtot are done
-            if (lane == 63) s_wtot[wave] = incl;
-            __syncthreads();
-            uint64_t before = carry;
-            for (uint32_t wv = 0; wv < wave; ++wv) before += s_wtot[wv];
-            const uint64_t woff = before + incl - bytes;
-            carry += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
-            if (live) {
-                adacomp_packet_layer_t rec;
-                rec.elem_offset = ld.elem_offset; rec.n_elems = ld.n_elems;
-                rec.L_T = ld.L_T; rec.n_bins = ld.n_bins; rec.word_bits = ld.word_bytes * 8u;
-                rec.scale = scale;
-                rec.n_selected = nsel;
-                rec.counts_offset = ld.counts_offset; rec.chunks_offset = ld.chunks_offset; rec.words_offset = woff;
-                reinterpret_cast<adacomp_packet_layer_t *>(packet + sizeof(adacomp_packet_header_t))[l] = rec;
-                for (uint64_t b = ld.counts_offset + uint64_t(ld.n_bins) * ld.word_bytes; b < ld.chunks_offset; ++b) packet[b] = 0;
-                const uint64_t chunks_end = ld.chunks_offset + 4ull * ld.n_chunks;
-                for (uint64_t b = chunks_end; b < pad16_dev(chunks_end); ++b) packet[b] = 0;
-                const uint64_t words_end = woff + uint64_t(nsel) * ld.word_bytes;
-                for (uint64_t b = words_end; b < pad16_dev(words_end); ++b)
-                    if (b < a.capacity) packet[b] = 0;
-            }
-            // total word count: per-wave sums through the same LDS slots
-            __syncthreads();
-            if (lane == 0) s_wtot[wave] = nsum;
-            __syncthreads();
-            nsel_all += uint64_t(s_wtot[0]) + s_wtot[1] + s_wtot[2] + s_wtot[3];
-        }
-        if (tid == 0) {
-            adacomp_packet_header_t h;
-            h.magic = ADACOMP_PACKET_MAGIC; h.version = ADACOMP_PACKET_VERSION;
-            h.status = carry > a.capacity ? ADACOMP_STATUS_TRUNCATED : ADACOMP_STATUS_COMPLETE;
-            h.n_layers = a.n_layers; h.total_bytes = carry; h.n_selected = nsel_all;
-            *reinterpret_cast<adacomp_packet_header_t *>(packet) = h;
-        }
+        place_header<FOLD>(a, packet, tile_out, layer_nsel, layer_scale, s_excl);
         return;
     }
 
@@ -673,6 +683,129 @@ __global__ __launch_bounds__(kWG) void k_place(const CompressArgs a)
     // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
     const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
     for (uint32_t t = t0 + 64u * sub; t < td.n_bins; t += 64u * kPlaceLanes) {
+        const uint32_t c = (td.first_bin + t) >> 6;
+        reinterpret_cast<uint32_t *>(packet + chunks_offset)[c] = base + chunk_rel[chunk_start + c];
+    }
+}
+
+// ==============================================================================================
+// k_place_tiled: the eager placement for tables with short bins.  Where L_T <= 64 several percent of
+// the elements are sent (7.9 % on the ResNet-50 table) and three quarters of the residue's 64-byte
+// lines hold a sent element, so correcting the residue word by word (a scattered read-modify-write
+// per word, as k_place does) moves far more than the lines themselves.  Here a workgroup owns one
+// compress tile: it places the tile's words, marks the sent elements in an LDS byte map (the
+// scheme of the lazy k_fused), and then streams over the tile's residue line by line: a line with a
+// mark is loaded whole, corrected with the same single float32 subtraction or addition, and written
+// back whole; a line without one is not touched.  Tiles that send only a few words (the fully
+// connected layers of such a table) and tiles that are not 16-byte aligned correct word by word.
+// ==============================================================================================
+constexpr uint32_t kTiledMinWords = 24;  // fewer words than this in a tile: word-by-word corrections
+
+__global__ __launch_bounds__(kWG) void k_place_tiled(const CompressArgs a)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lr = blockIdx.y;   // the learner of a batched call
+    uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
+    TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
+    uint32_t *const layer_nsel = reinterpret_cast<uint32_t *>(sb + a.o_layer_nsel);
+    float *const layer_scale = reinterpret_cast<float *>(sb + a.o_layer_scale);
+    const uint32_t *const chunk_rel = reinterpret_cast<const uint32_t *>(sb + a.o_chunk_rel);
+    const uint16_t *const stage_all = reinterpret_cast<const uint16_t *>(sb + a.o_stage);
+    uint8_t *const packet = a.packet[lr];
+
+    if (blockIdx.x == gridDim.x - 1) {
+        place_header<false>(a, packet, tile_out, layer_nsel, layer_scale, nullptr);
+        return;
+    }
+    const uint32_t tile = blockIdx.x;   // the grid has one workgroup per tile and one for the header
+    const TileDev td = a.tiles[tile];
+    const uint32_t l = td.layer();
+    const TileOut to = tile_out[tile];
+    const uint32_t cnt = to.count, base = to.base;
+    const uint32_t n = td.n_elems, T = td.L_T, M = td.magic;
+    const float scale = layer_scale[l];
+    const uint32_t wbytes = a.layers[l].word_bytes;
+    const uint64_t chunks_offset = a.layers[l].chunks_offset;
+    const uint32_t chunk_start = a.layers[l].chunk_start;
+    const uint16_t *__restrict__ stage = stage_all + td.stage_base;
+    float *__restrict__ rs = a.residue[lr] + td.elem_base;
+    const bool tiled = td.aligned() && cnt >= kTiledMinWords;   // uniform over the workgroup
+
+    __shared__ __attribute__((aligned(16))) uint8_t s_fix[16384];   // code of the word an element was sent with, or 0
+    __shared__ uint64_t s_part[kWG / 64u];
+    if (tiled)
+        for (uint32_t i = tid; i < (n + 15u) / 16u; i += kWG) reinterpret_cast<uint4 *>(s_fix)[i] = make_uint4(0u, 0u, 0u, 0u);
+
+    // first word of this layer = end of the fixed part + the (padded) word sections before it
+    uint64_t part = 0;
+    for (uint32_t m = tid; m < l; m += kWG) part += pad16_dev(uint64_t(layer_nsel[m]) * a.layers[m].word_bytes);
+#pragma unroll
+    for (uint32_t d = 32; d > 0; d >>= 1) {
+        const uint32_t lo = __shfl_xor(uint32_t(part), d, 64), hi = __shfl_xor(uint32_t(part >> 32), d, 64);
+        part += (uint64_t(hi) << 32) | lo;
+    }
+    if (lane == 0) s_part[wave] = part;
+    __syncthreads();   // the byte map is cleared, the partial sums are there
+    uint64_t woff = a.fixed_bytes;
+    for (uint32_t wv = 0; wv < kWG / 64u; ++wv) woff += s_part[wv];
+
+    for (uint32_t p = tid; p < cnt; p += kWG) {
+        const uint32_t s = stage[p];
+        const uint32_t e = s >> 2, code = s & 3u;
+        if (!(code & 1u) || e >= n) continue;   // codes are 1 or 3 and indices lie inside the tile
+        const uint32_t b = bin_of(e, T, M);
+        const uint32_t word = ((e - b * T) << 2) | code;   // index inside the bin, ternary code
+        const uint64_t at = woff + uint64_t(base + p) * wbytes;
+        if (at + wbytes <= a.capacity) {
+            if (wbytes == 1u) packet[at] = uint8_t(word);
+            else *reinterpret_cast<uint16_t *>(packet + at) = uint16_t(word);
+        }
+        if (tiled) s_fix[e] = uint8_t(code);
+        else {   // the sent elements' residue update of Algorithm 2, one element at a time
+            const float g = rs[e];
+            rs[e] = code == 1u ? g - scale : g + scale;
+        }
+    }
+
+    if (tiled) {
+        __syncthreads();   // the byte map is complete
+        // Lines of the residue: four consecutive 16-byte slots, the first on a 64-byte boundary.  The
+        // tile starts `shift` slots past such a boundary; virtual slot v = shift + (slot in the tile),
+        // so that the four lanes v & ~3 .. v | 3 share a line and decide together.
+        const uint32_t shift = uint32_t(reinterpret_cast<uintptr_t>(rs) >> 4) & 3u;
+        const uint32_t n_virtual = (shift + (n + 3u) / 4u + 3u) & ~3u;
+        for (uint32_t v = tid; v < n_virtual; v += kWG) {
+            const uint32_t e0 = (v - shift) * 4u;   // wraps to a huge value below the tile's start
+            const bool ok = v >= shift && e0 < n;
+            const uint32_t codes = ok ? *reinterpret_cast<const uint32_t *>(&s_fix[e0]) : 0u;   // bytes past n are 0
+            uint32_t any = codes;
+            any |= uint32_t(__shfl_xor(int(any), 1, 64));
+            any |= uint32_t(__shfl_xor(int(any), 2, 64));
+            if (!ok || any == 0u) continue;
+            if (e0 + 4u <= n) {
+                const vfloat4 r = load_stream4(rs + e0);
+                float g[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t code = (codes >> (8 * c)) & 3u;
+                    if (code == 1u) g[c] = g[c] - scale;
+                    else if (code == 3u) g[c] = g[c] + scale;
+                }
+                store_stream4(rs + e0, vfloat4{g[0], g[1], g[2], g[3]});
+            } else {   // the layer's last elements: what follows them is not ours to write
+                for (uint32_t c = 0; c < 4u && e0 + c < n; ++c) {
+                    const uint32_t code = (codes >> (8u * c)) & 3u;
+                    if (code == 1u) rs[e0 + c] = rs[e0 + c] - scale;
+                    else if (code == 3u) rs[e0 + c] = rs[e0 + c] + scale;
+                }
+            }
+        }
+    }
+
+    // chunks[c] = words of the layer in bins < 64 c, for the chunk starts inside this tile
+    const uint32_t t0 = (64u - (td.first_bin & 63u)) & 63u;
+    for (uint32_t t = t0 + 64u * tid; t < td.n_bins; t += 64u * kWG) {
         const uint32_t c = (td.first_bin + t) >> 6;
         reinterpret_cast<uint32_t *>(packet + chunks_offset)[c] = base + chunk_rel[chunk_start + c];
     }
@@ -1120,6 +1253,11 @@ int launch_place(const CompressArgs &a, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 wg(kWG);
+    if (a.place_tiled) {
+        if (a.fold_scan || a.place_mode != kPlaceEager) return ADACOMP_EINVAL;  // the host picks it for eager calls after a k_scan launch only
+        hipLaunchKernelGGL(k_place_tiled, dim3(a.n_tiles + 1u, a.n_learners), wg, 0, s, a);
+        return check_launch();
+    }
     if (a.fold_scan && (a.place_lanes != 64u || a.place_mode == kPlaceResidue || a.n_tiles > kFoldTiles || a.n_layers > kFoldLayers))
         return ADACOMP_EINVAL;  // the host picks the folded scan only where the kernel is built for it
     if (a.place_lanes == 64u) {

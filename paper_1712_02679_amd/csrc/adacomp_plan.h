@@ -147,6 +147,7 @@ struct CompressArgs {
     uint32_t place_lanes;               // lanes per tile in k_place: 16 or 64
     uint32_t place_mode;                // kPlaceEager / kPlaceWords / kPlaceResidue
     uint32_t fold_scan;                 // no k_scan launch: k_place computes word offsets and layer scales itself
+    uint32_t place_tiled;               // the placement is k_place_tiled: one workgroup per tile, residue corrected line by line
     uint32_t lazy;                      // k_fused applies the waiting residue corrections of the previous call
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2

@@ -176,6 +176,37 @@ def test_edge_tables_with_separate_scan_launch(H, oracle_lib, three_launch_compr
     H.run_lazy_parity(oracle_lib, wl, 2, 3, 2, seed=8, label="lazy " + name + ", separate scan")
 
 
+@pytest.fixture
+def word_by_word_placement():
+    """Tables with short bins and a separate scan launch correct the residue tile by tile in the
+    placement kernel; this sends them down the word-by-word placement of the other tables."""
+    import paper_1712_02679_amd as A
+    A.adacomp_tuning_place_tiled(False)
+    yield
+    A.adacomp_tuning_place_tiled(True)
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_TABLES))
+def test_edge_tables_with_word_by_word_placement(H, oracle_lib, three_launch_compress, word_by_word_placement, name):
+    wl = W.custom(name, EDGE_TABLES[name], dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 3, seed=18, label=name + ", separate scan, word-by-word placement", batch=True)
+
+
+def test_tiled_placement_alignment_and_density(H, oracle_lib, three_launch_compress):
+    """The tile-by-tile placement on layers that start at every 16-byte position inside a 64-byte line,
+    with ragged ends, dense and sparse tiles side by side (short and long bins in one table), all
+    elements sent, and a truncated packet; single and batched calls, free-running against the oracle."""
+    layers = [("a", 50 * 90 + 7, 50), ("b", 4 + 64 * 70, 64), ("c", 8 + 13 * 33 + 1, 13), ("d", 12 + 500 * 9, 500),
+              ("e", 7 * 641 + 3, 7), ("f", 16384 + 5, 16384), ("g", 3 * 1500 + 2, 3), ("h", 1 * 4100, 1)]
+    wl = W.custom("tiled_alignment", layers, dist="normal_outliers")
+    H.run_parity(oracle_lib, wl, 3, 4, seed=21, batch=True)
+    H.run_parity(oracle_lib, wl, 2, 3, seed=22)
+    # every element sent (equal magnitudes): every line of every tile is rewritten
+    n = wl.n_total
+    same = lambda k, t: np.where((np.arange(n) + k + t) % 3 == 0, -0.5, 0.5).astype(f32)
+    H.run_parity(oracle_lib, wl, 2, 2, grads=same, label="tiled_alignment all sent", batch=True)
+
+
 def test_scan_paths_can_alternate(H, oracle_lib):
     """The folded and the separate scan leave the same state behind: calls on one workspace may
     alternate between them, also while lazy corrections wait."""
