@@ -1,8 +1,9 @@
 /*
  * adacomp_oracle.c -- see adacomp_oracle.h.  TEST INFRASTRUCTURE ONLY: the slow CPU checker.
  *
- * Plain C, one thread, one loop per step of Algorithm 2 of the AdaComp paper, in the paper's
- * order and notation (G, H, T, g_max, Gq, residue).  No blocking, no fusion, no reordering.
+ * Plain C, one thread.  The steps of Algorithm 2 of the AdaComp paper are taken in the paper's
+ * order and notation (G, H, T, g_max, Gq, residue), each as a small function of its own and a
+ * driver that calls them; no blocking, no fusion, no reordering.
  * Build without value-changing options: gcc -O2 -ffp-contract=off, no fast-math.
  */
 #include "adacomp_oracle.h"
@@ -19,8 +20,57 @@
 #define LT_MAX 16384u
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 2, one layer.
+ * Algorithm 2, one layer: small pieces first, then the driver that strings them together.
  * ---------------------------------------------------------------------------------------- */
+
+/* Elements [*lo, *hi) of bin i when a vector of n elements is cut into bins of T (section
+ * "Adaptive Residual Gradient Compression (AdaComp) Technique": a uniform cut; the last bin is
+ * short when T does not divide n). */
+static void bin_range(uint64_t i, uint32_t T, uint64_t n, uint64_t *lo, uint64_t *hi)
+{
+    *lo = i * T;
+    *hi = *lo + T < n ? *lo + T : n;
+}
+
+/* g_max of one bin: the largest absolute value of G over [lo, hi). */
+static float bin_max_abs(const float *G, uint64_t lo, uint64_t hi)
+{
+    float m = 0.0f;
+    for (uint64_t index = lo; index < hi; ++index) {
+        float a = fabsf(G[index]);
+        if (a > m) m = a;
+    }
+    return m;
+}
+
+/* The quantiser's scale: the average of the g_max vector over all bins of the layer (section
+ * "Pseudo code"), accumulated in double in bin order and rounded to float once. */
+static float mean_of_gmax(const float *gmax, uint64_t n_bins)
+{
+    double sum = 0.0;
+    for (uint64_t i = 0; i < n_bins; ++i) sum += (double)gmax[i];
+    return (float)(sum / (double)n_bins);
+}
+
+/* The soft-threshold operand for one element: the stored G plus dW once more.  That is residue +
+ * 2 dW, the paper's choice among the factors 1.5 - 3.0 it studied; another factor f gives residue +
+ * f dW, formed as G + (f - 1) dW with one multiplication and one addition. */
+static float soft_operand(float g, float dw, float soft_factor)
+{
+    if (soft_factor == 2.0f) return g + dw;
+    float f_minus_1 = soft_factor - 1.0f;
+    float extra = f_minus_1 * dw;
+    return g + extra;
+}
+
+/* Is the element sent?  m is its bin's g_max. */
+static int is_sent(int rule, float g, float h, float m)
+{
+    if (rule == ADACOMP_ORACLE_RULE_LITERAL) return fabsf(h) >= m;
+    if (rule == ADACOMP_ORACLE_RULE_LS) return (g != 0.0f) && (fabsf(g) >= m);
+    return (g != 0.0f) && (fabsf(h) >= m || fabsf(g) >= m);
+}
+
 long long adacomp_oracle_pack_layer(const float *residue_in, const float *dW, uint64_t n, uint32_t T,
                                     int rule, float soft_factor, float *G, float *H, float *gmax,
                                     float *scale, uint8_t *selected, float *residue_out)
@@ -30,61 +80,38 @@ long long adacomp_oracle_pack_layer(const float *residue_in, const float *dW, ui
     if (rule < 0 || rule > 2) return -1;
     if (!(soft_factor >= 1.0f && soft_factor <= 16.0f)) return -1;
 
-    uint64_t n_bins = (n + T - 1) / T; /* last bin may be short */
+    uint64_t n_bins = (n + T - 1) / T;
 
-    /* G <- residue + dW */
-    for (uint64_t index = 0; index < n; ++index) G[index] = residue_in[index] + dW[index];
-
-    /* H <- G + dW   (two float additions: the stored G is used).  That is residue + 2 dW, the
-     * paper's choice among the factors 1.5 - 3.0 it studied; for another factor f the operand is
-     * residue + f dW, formed as G + (f - 1) dW with one multiplication and one addition. */
-    if (soft_factor == 2.0f) {
-        for (uint64_t index = 0; index < n; ++index) H[index] = G[index] + dW[index];
-    } else {
-        float f_minus_1 = soft_factor - 1.0f;
-        for (uint64_t index = 0; index < n; ++index) {
-            float extra = f_minus_1 * dW[index];
-            H[index] = G[index] + extra;
-        }
+    /* the two element-wise vectors */
+    for (uint64_t index = 0; index < n; ++index) {
+        G[index] = residue_in[index] + dW[index];
+        H[index] = soft_operand(G[index], dW[index], soft_factor);
     }
 
-    /* first loop over bins: g_max(i) = largest absolute value of G in bin i */
+    /* every bin's maximum, then the one scale of the layer */
     for (uint64_t i = 0; i < n_bins; ++i) {
-        uint64_t lo = i * T, hi = lo + T < n ? lo + T : n;
-        float m = 0.0f;
-        for (uint64_t index = lo; index < hi; ++index) {
-            float a = fabsf(G[index]);
-            if (a > m) m = a;
-        }
-        gmax[i] = m;
+        uint64_t lo, hi;
+        bin_range(i, T, n, &lo, &hi);
+        gmax[i] = bin_max_abs(G, lo, hi);
     }
-
-    /* the quantiser's scale: average of the g_max vector (section "Pseudo code") */
-    double sum = 0.0;
-    for (uint64_t i = 0; i < n_bins; ++i) sum += (double)gmax[i];
-    float s = (float)(sum / (double)n_bins);
+    float s = mean_of_gmax(gmax, n_bins);
     *scale = s;
 
-    /* second loop: bins, then indices within each bin */
+    /* bin by bin, index by index: compare with the bin's maximum, quantise what is sent, and leave
+     * the rest of G (all of it when nothing is sent) as the new residue */
     long long n_sent = 0;
     for (uint64_t i = 0; i < n_bins; ++i) {
-        uint64_t lo = i * T, hi = lo + T < n ? lo + T : n;
+        uint64_t lo, hi;
+        bin_range(i, T, n, &lo, &hi);
         for (uint64_t index = lo; index < hi; ++index) {
             float g = G[index];
-            int send;
-            if (rule == ADACOMP_ORACLE_RULE_LITERAL)
-                send = fabsf(H[index]) >= gmax[i];
-            else if (rule == ADACOMP_ORACLE_RULE_LS)
-                send = (g != 0.0f) && (fabsf(g) >= gmax[i]);
-            else
-                send = (g != 0.0f) && (fabsf(H[index]) >= gmax[i] || fabsf(g) >= gmax[i]);
-            if (send) {
-                float Gq = copysignf(s, g); /* Quantize: sign bit and the layer scale */
+            if (is_sent(rule, g, H[index], gmax[i])) {
+                float Gq = copysignf(s, g); /* sign bit and the layer scale */
                 residue_out[index] = g - Gq;
                 selected[index] = 1;
                 ++n_sent;
             } else {
-                residue_out[index] = g; /* no transmission */
+                residue_out[index] = g;
                 selected[index] = 0;
             }
         }
