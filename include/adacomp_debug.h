@@ -46,7 +46,9 @@ int adacomp_tuning_unpack_min_groups(uint32_t n_groups);
 /* Tuning knob of the compress calls, read at every call.  Tables of up to 512 compress tiles and
  * 16 layers skip the separate scan launch (layer scales, word offsets): the placement kernel works
  * them out itself.  enable = 0 makes such tables take the three-launch path of the large ones;
- * non-zero restores the default.  Results do not depend on it.  Process-wide; not synchronised with
+ * non-zero restores the default.  Results do not depend on it while the float64 sum of every layer's
+ * g_max vector is exact (see "Arithmetic" in adacomp.h); beyond that a layer scale may differ in its
+ * last bit between the two paths.  Process-wide; not synchronised with
  * calls on other threads.  Returns ADACOMP_OK. */
 int adacomp_tuning_fold_scan(int enable);
 

@@ -109,8 +109,11 @@ def layer_mask(table, n_total):
     return m
 
 
-def compare_packet(got_buf, want, capacity, tag):
-    """got_buf: device packet buffer (with poison tail); want: oracle packet bytes."""
+def compare_packet(got_buf, want, capacity, tag, strict=True):
+    """got_buf: device packet buffer (with poison tail); want: oracle packet bytes.
+    Everything but the scales must be bit-equal and the scales within 1e-6 relative.  strict: the
+    scales must be bit-equal too (what every case expects whose float64 sum of g_max is exact);
+    otherwise the return value says whether they were."""
     h = pf.header(got_buf)
     assert int(h["total_bytes"]) == want.size, f"{tag}: total_bytes {int(h['total_bytes'])} != oracle {want.size}"
     got = got_buf[:want.size]
@@ -127,22 +130,28 @@ def compare_packet(got_buf, want, capacity, tag):
             assert abs(sg - sw) <= 1e-6 * abs(sw), f"{tag}: layer {li} scale {sg!r} vs oracle {sw!r}"
         bad = np.flatnonzero(masked_g != masked_w)
         assert bad.size == 0, f"{tag}: packet differs from the oracle at byte {bad[0]} ({bad.size} bytes differ)"
-        raise AssertionError(f"{tag}: packet equal except for the last bits of a scale "
-                             "(inside the 1e-6 bar, but bit equality was expected)")
+        if strict:
+            raise AssertionError(f"{tag}: packet equal except for the last bits of a scale "
+                                 "(inside the 1e-6 bar, but bit equality was expected)")
+        assert np.all(got_buf[want.size:] == POISON), f"{tag}: bytes after total_bytes were written"
+        return False
     # nothing written past the packet end / past the capacity
     tail = got_buf[want.size:]
     assert np.all(tail == POISON), f"{tag}: bytes after total_bytes were written"
     pf.parse(got)  # structural invariants of the container
+    return True
 
 
-def compare_residue(got, want, mask, scale_hint, tag):
+def compare_residue(got, want, mask, scale_hint, tag, strict=True):
     if np.array_equal(got[mask].view(np.uint32), want[mask].view(np.uint32)):
-        return
+        return True
     d = np.abs(got[mask].astype(np.float64) - want[mask])
     tol = 1e-6 * np.maximum(np.abs(want[mask]), scale_hint)
     worst = int(np.argmax(d - tol))
     assert np.all(d <= tol), f"{tag}: residue differs beyond 1e-6 at masked index {worst}: {got[mask][worst]} vs {want[mask][worst]}"
-    raise AssertionError(f"{tag}: residue within 1e-6 but not bit-equal (max diff {d.max():.3e})")
+    if strict:
+        raise AssertionError(f"{tag}: residue within 1e-6 but not bit-equal (max diff {d.max():.3e})")
+    return False
 
 
 def run_parity(oracle_lib, wl, n_learners, n_steps, seed=0, step_locked=False, grads=None,
