@@ -4,7 +4,7 @@
 // adacomp_unpack_accumulate per step, a single-learner adacomp_compress, then one
 // adacomp_unpack_update, then two steps of adacomp_compress_batch_lazy and an adacomp_residue_sync;
 // packets, residues, the dense sum and the updated weights must equal the
-// oracle's byte for byte.  Built by tests/c_driver/build.py (called from the repository's build
+// oracle's byte for byte; last, two single-learner steps through adacomp_compress_static.  Built by tests/c_driver/build.py (called from the repository's build
 // entry point), run by tests/test_gpu_parity.py::test_caller_written_in_c.
 #include <hip/hip_runtime.h>
 
@@ -148,6 +148,22 @@ int main()
     for (uint32_t k = 0; k < n_learners; ++k) {
         HIP_OK(hipMemcpy(got.data(), d_res[k], n_total * 4, hipMemcpyDeviceToHost));
         if (std::memcmp(got.data(), res[k].data(), n_total * 4) != 0) { std::printf("after the sync: residue of learner %u differs\n", k); return 4; }
+    }
+
+    // two more mini-batches of learner 1 through the entry point that takes no workspace and
+    // allocates nothing (its scratch is a static array inside the library), on the same stream
+    for (uint32_t t = 0; t < 2; ++t) {
+        for (size_t i = 0; i < n_total; ++i) grad[1][i] = draw((uint64_t(300 + t) << 40) | i, 0.02f);
+        HIP_OK(hipMemcpy(d_grad[1], grad[1].data(), n_total * 4, hipMemcpyHostToDevice));
+        std::memset(want_pk[1].data(), 0, bound);
+        pk_bytes[1] = adacomp_oracle_compress(otable, n_layers, grad[1].data(), res[1].data(), want_pk[1].data(), bound, 0, 2.0f);
+        if (pk_bytes[1] <= 0) return 1;
+        LIB_OK(adacomp_compress_static(table, n_layers, d_grad[1], d_res[1], d_pk[1], bound, stream));
+        HIP_OK(hipStreamSynchronize(stream));
+        HIP_OK(hipMemcpy(got_pk[1].data(), d_pk[1], size_t(pk_bytes[1]), hipMemcpyDeviceToHost));
+        if (std::memcmp(got_pk[1].data(), want_pk[1].data(), size_t(pk_bytes[1])) != 0) { std::printf("static call %u: packet differs\n", t); return 4; }
+        HIP_OK(hipMemcpy(got.data(), d_res[1], n_total * 4, hipMemcpyDeviceToHost));
+        if (std::memcmp(got.data(), res[1].data(), n_total * 4) != 0) { std::printf("static call %u: residue differs\n", t); return 4; }
     }
 
     LIB_OK(adacomp_workspace_release(ws));

@@ -73,3 +73,53 @@ def test_static_scratch_entry_point(oracle_lib):
     assert e.value.code == binding.ETOOBIG
     # and the array still serves the next call
     _case(A, oracle_lib, W.workload(1), 2, seed=9)
+
+
+def test_static_scratch_entry_point_in_a_hip_graph(oracle_lib):
+    """What the entry point is for: once its static array holds the tile tables of a layer table (one
+    call outside the capture), a call only launches kernels, so it can be captured in a HIP graph.  The
+    graph is replayed several times with eager work and synchronisations in between; every replay is
+    checked against the free-running oracle."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1712_02679_amd as A
+    dev = "cuda:0"
+    wl = W.workload(2)
+    table, n = wl.table(), wl.n_total
+    bound = A.adacomp_packet_bound(table)
+    g_in = torch.zeros(n, dtype=torch.float32, device=dev)
+    R = torch.zeros(n, dtype=torch.float32, device=dev)
+    pk = torch.empty(bound + 64, dtype=torch.uint8, device=dev)
+    # eager neighbour on a workspace of its own, run between the replays
+    ws = torch.zeros(A.adacomp_workspace_bytes(table), dtype=torch.uint8, device=dev)
+    A.adacomp_workspace_init(table, ws)
+    R2 = torch.zeros(n, dtype=torch.float32, device=dev)
+    pk2 = torch.empty(bound, dtype=torch.uint8, device=dev)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):   # outside the capture: writes the tile tables into the static array
+            A.adacomp_compress_static(table, g_in, R, pk, packet_capacity=bound)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            A.adacomp_compress_static(table, g_in, R, pk, packet_capacity=bound)
+        R.zero_()
+        R_cpu = np.zeros(n, f32)
+        for t in range(4):
+            print(f"[no_alloc] graph replay {t}", flush=True)
+            g_np = W.gradient(wl, 0, t, seed=31)
+            g_in.copy_(torch.from_numpy(g_np))
+            pk.fill_(POISON)
+            graph.replay()
+            torch.cuda.synchronize()
+            want = oracle_lib.compress(table, g_np, R_cpu)
+            got = pk.cpu().numpy()
+            assert np.array_equal(got[:want.size], want), f"replay {t}: packet differs from the oracle"
+            assert np.all(got[want.size:] == POISON)
+            assert np.array_equal(R.cpu().numpy().view(np.uint32), R_cpu.view(np.uint32)), f"replay {t}: residue"
+            A.adacomp_compress(table, g_in, R2, pk2, ws)
+            torch.cuda.synchronize()
+    finally:
+        A.adacomp_workspace_release(ws)
