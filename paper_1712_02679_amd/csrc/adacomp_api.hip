@@ -102,12 +102,16 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
         // 16 elements per thread (tiles of 4096 elements) unless a bin is longer: then 64 per thread
         // (16384).  Tiles of 8192 elements streamed at less than half the rate of either on MI355X
         // (measured on a plain triad), so there is no class in between.
-        const int cls = T > 4096u ? 1 : 0;
+        // Tile starts are float4-aligned when a tile holds a multiple of a = 4 / gcd(L_T, 4) bins.  Bin
+        // lengths that are odd (a = 4) or twice an odd number (a = 2) and too long for a such bins to fit
+        // 4096 elements take the larger class when they fit there: unaligned tiles fall back to 4-byte
+        // accesses, which stream at 44 % of the HBM peak instead of 71-77 %.
+        const uint32_t a = 4u / gcd_u32(T, 4u);
+        const int cls = (T > 4096u || (uint64_t(a) * T > 4096u && uint64_t(a) * T <= 16384u)) ? 1 : 0;
         const uint32_t cap = cls ? 16384u : 4096u;
         uint32_t bpt = (cls ? cap : small_cap) / T;
         if (bpt == 0) bpt = 1;                        // a bin of up to cap elements always fits its class
         if (bpt > kMaxTileBins) bpt = kMaxTileBins;
-        const uint32_t a = 4u / gcd_u32(T, 4u);       // bins per tile must be a multiple of a for float4 alignment
         if (bpt < a && uint64_t(a) * T <= cap) bpt = a;
         if (bpt >= a) bpt -= bpt % a;
         const uint32_t nt = (n_bins + bpt - 1) / bpt;
@@ -133,6 +137,19 @@ int build_plan(const adacomp_layer_t *layers, uint32_t n_layers, bool tables, Pl
                 td.first_bin = first_bin;
                 td.layer_flags = l | (uint32_t(cls) << 24) | ((e0 % 4 == 0) ? 0x80000000u : 0u);
                 p.ctiles.push_back(td);
+            }
+        }
+        // unaligned tiles of the larger class keep 16-byte accesses when the tile still fits with its
+        // misalignment added (all but bins of 16382 or 16383 elements); independent of `tables`, so
+        // that every plan of a table says the same
+        if (cls == 1 && (uint64_t(bpt) * T) % 4 != 0) {
+            for (uint32_t t = 0; t < nt; ++t) {
+                const uint64_t e0 = uint64_t(t) * bpt * T;
+                const uint32_t sk = uint32_t(e0 % 4), ne = uint32_t(std::min<uint64_t>(uint64_t(bpt) * T, n - e0));
+                if (sk != 0 && ne + sk <= 16384u) {
+                    p.has_shifted_tiles = true;
+                    if (tables) p.ctiles[p.ctiles.size() - nt + t].layer_flags |= sk << 25;
+                }
             }
         }
         p.stage_entries += full_stretch * (nt - 1) + ((n - full_tile * (nt - 1) + 3u) & ~uint64_t(3));
@@ -304,7 +321,7 @@ int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *work
     out.elem_span = p.elem_span; out.n_elems_total = p.n_elems_total; out.stage_entries = p.stage_entries;
     out.fixed_bytes = p.fixed_bytes; out.bound_bytes = p.bound_bytes;
     for (int c = 0; c < 2; ++c) out.n_class_tiles[c] = p.n_class_tiles[c];
-    out.has_short_bins = p.has_short_bins;
+    out.has_short_bins = p.has_short_bins; out.has_shifted_tiles = p.has_shifted_tiles;
     out.ws = p.ws;
     return ADACOMP_OK;
 }
@@ -486,6 +503,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     // tables with short bins send a large share of their elements: the eager placement then corrects
     // the residue tile by tile, whole lines at a time (k_place_tiled), instead of word by word
     a.place_tiled = (g_place_tiled.load(std::memory_order_relaxed) && p.has_short_bins && !a.fold_scan && !lazy) ? 1u : 0u;
+    a.shift = (p.has_shifted_tiles && !corrections_wait) ? 1u : 0u;
     a.rule = rule;
     a.soft_factor_minus_1 = soft_factor - 1.0f;
     a.capacity = packet_capacity;

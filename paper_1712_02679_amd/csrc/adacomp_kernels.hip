@@ -63,6 +63,15 @@ __device__ __forceinline__ void buffer_store_stream4(__amdgpu_buffer_rsrc_t rsrc
 {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(vuint4, v), rsrc, int(elem * 4u), 0, kAuxStream);
 }
+// one element through the same descriptor (the first and last slot of a tile that is not 16-byte aligned)
+__device__ __forceinline__ float buffer_load1(__amdgpu_buffer_rsrc_t rsrc, uint32_t elem)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, int(elem * 4u), 0, 0));
+}
+__device__ __forceinline__ void buffer_store1(__amdgpu_buffer_rsrc_t rsrc, uint32_t elem, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, int(elem * 4u), 0, 0);
+}
 
 __device__ __forceinline__ uint32_t bin_of(uint32_t e, uint32_t L_T, uint32_t magic)
 {
@@ -108,9 +117,15 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // LAZY = true: the residue corrections of the learner's previous call (residue <- G - Gq at the
 // elements it sent) are still waiting in the scratch block instead of having been written (the host
 // knows); they are applied here, to the residue values in registers, before anything else.
-template <int J, int WAVES, bool VARIANT, bool LAZY>
+// SHIFT = true (launches over tiles of 16384 elements that hold bins of an odd length, or of twice an
+// odd length): a tile that starts `skip` = 1..3 elements past a 16-byte boundary still moves whole
+// 16-byte slots.  Slot q of the tile then covers the elements 4 q - skip .. 4 q + 3 - skip: the first
+// slot begins in the tile before (those elements are left alone: loaded as zero, never stored) and
+// everything after it is aligned.  With 4-byte accesses such tiles streamed at 44 % of the HBM peak.
+template <int J, int WAVES, bool VARIANT, bool LAZY, bool SHIFT = false>
 __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
 {
+    static_assert(!(SHIFT && LAZY), "the lazy kernel keeps 4-byte accesses on unaligned tiles");
     constexpr uint32_t WG = uint32_t(WAVES) * 64u;  // threads of the workgroup: a tile is J * WG float4 slots
     static_assert(J * WAVES <= 64, "the per-row word totals are scanned by one wave");
     // one-dimensional grid, learner-major: workgroups are dispatched in index order, so a batched
@@ -141,7 +156,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform across the wave
     const uint32_t n = td.n_elems, T = td.L_T, M = td.magic, nb = td.n_bins;
-    const bool vec = td.aligned();
+    const uint32_t skip = SHIFT ? td.skip() : 0u;         // elements of the first slot that belong to the tile before
+    const bool vec = td.aligned() || (SHIFT && skip != 0u);
 
     for (uint32_t i = tid; i < nb; i += WG) { s_gmax[i] = 0u; s_cnt[i] = 0u; }
 
@@ -152,8 +168,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     float r[J][4], w[J][4];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
-        if (vec && e0 + 4u <= n) {
+        const uint32_t f0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t e0 = f0 - skip;   // wraps to a huge value in the first slot of a shifted tile: its valid elements wrap back
+        if (vec && f0 >= skip && e0 + 4u <= n) {
             const vfloat4 rv = load_stream4(rs + e0);
             const vfloat4 wv = load_stream4(gr + e0);
             r[j][0] = rv.x; r[j][1] = rv.y; r[j][2] = rv.z; r[j][3] = rv.w;
@@ -205,7 +222,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     uint32_t mb[J][4];  // bits of max(|G|, |H|): what is compared with g_max
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t f0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t e0 = f0 - skip;
         float G[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -223,7 +241,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
             else if (VARIANT && a.rule == ADACOMP_RULE_LOCAL_SELECTION) mb[j][c] = ag;     // bin maxima only
             else mb[j][c] = ag > ah ? ag : ah;
         }
-        if (vec && e0 + 4u <= n) {
+        if (vec && f0 >= skip && e0 + 4u <= n) {
             store_stream4(rs + e0, vfloat4{G[0], G[1], G[2], G[3]});
         } else {
 #pragma unroll
@@ -237,13 +255,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     // ---- first loop of Algorithm 2: g_max(i) per bin -------------------------------------------
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t f0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t e0 = f0 - skip;
         if (WAVES == 16) {
             // Long bins: the 256 elements of a wave's row of slots nearly always lie in one bin, and
             // 64 lanes that bring their maxima to one LDS address are served one after the other
             // (2 cycles each, measured).  The wave reduces first; one lane goes to the LDS.
-            const uint32_t w0 = (uint32_t(j) * WG + wave * 64u) * 4u;   // uniform: first element of the row
-            if (w0 < n) {
+            const uint32_t w0f = (uint32_t(j) * WG + wave * 64u) * 4u;  // uniform: first slot of the row
+            const uint32_t w0 = w0f - skip;                              // its first element (the row that holds a shifted tile's first slot takes the path below)
+            if (w0f >= skip && w0 < n) {
                 const uint32_t w1 = w0 + 255u < n ? w0 + 255u : n - 1u;
                 const uint32_t bw = bin_of(w0, T, M);
                 if (bw == bin_of(w1, T, M)) {
@@ -257,7 +277,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
                 }
             }
         }
-        if (e0 < n) {
+        if (SHIFT && f0 < skip) {   // the first slot of a shifted tile: only the elements from skip on are the tile's
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (e0 + uint32_t(c) < n) atomicMax(&s_gmax[bin_of(e0 + c, T, M)], gb[j][c] & 0x7FFFFFFFu);
+        } else if (e0 < n) {
             const uint32_t e3 = e0 + 3u < n ? e0 + 3u : n - 1u;
             const uint32_t b0 = bin_of(e0, T, M), b3 = bin_of(e3, T, M);
             if (b0 == b3) {
@@ -280,9 +304,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     uint32_t wtot[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t f0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t e0 = f0 - skip;
         uint32_t f = 0u;
-        if (e0 < n) {
+        if (e0 < n || (SHIFT && f0 < skip)) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint32_t e = e0 + uint32_t(c);
@@ -318,7 +343,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     uint16_t *__restrict__ stage = stage_all + td.stage_base;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u;
+        const uint32_t e0 = (uint32_t(j) * WG + tid) * 4u - skip;
         uint32_t pos = __shfl(row_incl, j * WAVES + int(wave), 64) - wtot[j] + before[j];
         const uint32_t f = flags[j];
         if (f) {
@@ -1157,48 +1182,65 @@ __global__ __launch_bounds__(kWG, (KIND == 2 ? 4 : 6)) void k_unpack(const Unpac
     }
     __syncthreads();
 
+    float *const W = MODE == 1 ? a.weights + ut.elem_base : nullptr;
+    float *const S1 = MODE == 1 ? a.state1 + ut.elem_base : nullptr;
     const __amdgpu_buffer_rsrc_t w_buf = tile_buffer(MODE == 2 ? a.weights + ut.elem_base : out, MODE == 2 ? n : 0u);
     const __amdgpu_buffer_rsrc_t s1_buf = tile_buffer(MODE == 2 ? a.state1 + ut.elem_base : out, MODE == 2 ? n : 0u);
     const __amdgpu_buffer_rsrc_t s2_buf = tile_buffer(MODE == 2 ? a.state2 + ut.elem_base : out, MODE == 2 ? n : 0u);
-    for (uint32_t i = tid * 4u; i < n; i += kWG * 4u) {
-        const float4 v = *reinterpret_cast<const float4 *>(&s_acc[i]);
-        const bool full = vec && i + 4u <= n;
+    // The write-out moves 16-byte slots of memory whatever the tile's alignment.  A tile that starts
+    // `skip` elements past a 16-byte boundary reads its accumulators from the LDS tile at the matching
+    // offset (four 4-byte reads per slot instead of one 16-byte read): slot f (a multiple of 4) holds
+    // the elements f - skip .. f + 3 - skip; in the first slot that wraps below zero, and `< n` on the
+    // wrapped value tells the elements that are the tile's.  (With 4-byte accesses to memory such
+    // tiles were written at 3.1 instead of 5 TB/s.)
+    // (The Adam epilogue sits at its register limit and keeps 4-byte accesses on unaligned tiles: the
+    // few registers this costs spilled there and slowed the aligned case by 4 %.)
+    const uint32_t skip = MODE == 2 ? 0u : uint32_t(ut.elem_base) & 3u;
+    for (uint32_t f = tid * 4u; f < n + skip; f += kWG * 4u) {
+        const uint32_t e = f - skip;
+        const bool full = (MODE != 2 || vec) && f >= skip && e + 4u <= n;
+        float sum[4];
+        if (skip == 0u) {
+            const float4 v = *reinterpret_cast<const float4 *>(&s_acc[f]);
+            sum[0] = v.x; sum[1] = v.y; sum[2] = v.z; sum[3] = v.w;
+        } else {
+#pragma unroll
+            for (uint32_t c = 0; c < 4u; ++c) sum[c] = e + c < n ? s_acc[e + c] : 0.f;
+        }
         if (a.write_dense) {
-            if (full) store_stream4(out + i, vfloat4{v.x, v.y, v.z, v.w});
+            if (full) store_stream4(out + e, vfloat4{sum[0], sum[1], sum[2], sum[3]});
             else {
-                out[i] = v.x;
-                if (i + 1u < n) out[i + 1] = v.y;
-                if (i + 2u < n) out[i + 2] = v.z;
-                if (i + 3u < n) out[i + 3] = v.w;
+#pragma unroll
+                for (uint32_t c = 0; c < 4u; ++c)
+                    if (e + c < n) out[e + c] = sum[c];
             }
         }
         if (MODE != 0) {
-            float *__restrict__ wp = a.weights + ut.elem_base + i;
-            float *__restrict__ p1 = a.state1 + ut.elem_base + i;
-            float *__restrict__ p2 = MODE == 2 ? a.state2 + ut.elem_base + i : nullptr;
-            const float sum[4] = {v.x, v.y, v.z, v.w};
             if (full) {
                 vfloat4 w4, s14, s24 = vfloat4{0.f, 0.f, 0.f, 0.f};
-                if (MODE == 2) { w4 = buffer_load_stream4(w_buf, i); s14 = buffer_load_stream4(s1_buf, i); s24 = buffer_load_stream4(s2_buf, i); }
-                else { w4 = load_stream4(wp); s14 = load_stream4(p1); }
+                if (MODE == 2) { w4 = buffer_load_stream4(w_buf, e); s14 = buffer_load_stream4(s1_buf, e); s24 = buffer_load_stream4(s2_buf, e); }
+                else { w4 = load_stream4(W + e); s14 = load_stream4(S1 + e); }
                 float w[4] = {w4.x, w4.y, w4.z, w4.w}, s1[4] = {s14.x, s14.y, s14.z, s14.w}, s2[4] = {s24.x, s24.y, s24.z, s24.w};
 #pragma unroll
                 for (int c = 0; c < 4; ++c) apply_update<MODE>(a, sum[c], w[c], s1[c], s2[c]);
                 if (MODE == 2) {
-                    buffer_store_stream4(w_buf, i, vfloat4{w[0], w[1], w[2], w[3]});
-                    buffer_store_stream4(s1_buf, i, vfloat4{s1[0], s1[1], s1[2], s1[3]});
-                    buffer_store_stream4(s2_buf, i, vfloat4{s2[0], s2[1], s2[2], s2[3]});
+                    buffer_store_stream4(w_buf, e, vfloat4{w[0], w[1], w[2], w[3]});
+                    buffer_store_stream4(s1_buf, e, vfloat4{s1[0], s1[1], s1[2], s1[3]});
+                    buffer_store_stream4(s2_buf, e, vfloat4{s2[0], s2[1], s2[2], s2[3]});
                 } else {
-                    store_stream4(wp, vfloat4{w[0], w[1], w[2], w[3]});
-                    store_stream4(p1, vfloat4{s1[0], s1[1], s1[2], s1[3]});
+                    store_stream4(W + e, vfloat4{w[0], w[1], w[2], w[3]});
+                    store_stream4(S1 + e, vfloat4{s1[0], s1[1], s1[2], s1[3]});
                 }
             } else {
-                for (uint32_t c = 0; c < 4u && i + c < n; ++c) {
-                    float w = wp[c], s1 = p1[c], s2 = MODE == 2 ? p2[c] : 0.f;
+                for (uint32_t c = 0; c < 4u; ++c) {
+                    const uint32_t ec = e + c;   // wraps back into the tile for the elements of the first slot that are the tile's
+                    if (ec >= n) continue;
+                    float w, s1, s2 = 0.f;
+                    if (MODE == 2) { w = buffer_load1(w_buf, ec); s1 = buffer_load1(s1_buf, ec); s2 = buffer_load1(s2_buf, ec); }
+                    else { w = W[ec]; s1 = S1[ec]; }
                     apply_update<MODE>(a, sum[c], w, s1, s2);
-                    wp[c] = w;
-                    p1[c] = s1;
-                    if (MODE == 2) p2[c] = s2;
+                    if (MODE == 2) { buffer_store1(w_buf, ec, w); buffer_store1(s1_buf, ec, s1); buffer_store1(s2_buf, ec, s2); }
+                    else { W[ec] = w; S1[ec] = s1; }
                 }
             }
         }
@@ -1235,9 +1277,11 @@ int launch_fused(const CompressArgs &a, int jcode, void *stream)
         else hipLaunchKernelGGL((k_fused<4, 16, false, true>), grid, wg, 0, s, a);
     } else if (!variant) {
         if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, false>), grid, wg, 0, s, a);
+        else if (a.shift) hipLaunchKernelGGL((k_fused<4, 16, false, false, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<4, 16, false, false>), grid, wg, 0, s, a);
     } else {
         if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, true, false>), grid, wg, 0, s, a);
+        else if (a.shift) hipLaunchKernelGGL((k_fused<4, 16, true, false, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<4, 16, true, false>), grid, wg, 0, s, a);
     }
     return check_launch();

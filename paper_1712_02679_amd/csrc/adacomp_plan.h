@@ -43,9 +43,13 @@ struct TileDev {
     uint16_t n_elems;     // elements in the tile, <= 4096 or 16384 by register class
     uint16_t n_bins;      // bins in the tile, <= kMaxTileBins
     uint32_t first_bin;   // index of the tile's first bin inside the layer
-    uint32_t layer_flags; // bits 0..23 layer, bit 24 register class (0: 4096-element tiles, 1: 16384), bit 31 aligned
+    uint32_t layer_flags; // bits 0..23 layer, bit 24 register class (0: 4096-element tiles, 1: 16384), bits 25..26 skip, bit 31 aligned
     __host__ __device__ uint32_t layer() const { return layer_flags & 0xFFFFFFu; }
     __host__ __device__ uint32_t jcode() const { return (layer_flags >> 24) & 1u; }
+    // skip: for a tile of the larger class that is not 16-byte aligned but fits its class with the
+    // misalignment added, the number of elements (1..3) between the 16-byte boundary below the tile
+    // and its first element; 0 for aligned tiles and for unaligned ones that take 4-byte accesses
+    __host__ __device__ uint32_t skip() const { return (layer_flags >> 25) & 3u; }
     __host__ __device__ bool aligned() const { return (layer_flags >> 31) != 0; }
 };
 static_assert(sizeof(TileDev) == 32, "TileDev layout");
@@ -112,6 +116,7 @@ struct Plan {
     uint32_t n_class_tiles[2] = {0, 0};  // compress tiles of 4096 / of 16384 elements
     std::vector<uint32_t> cclass;        // compress tile indices, the 4096-element ones first (tables with both kinds)
     bool has_short_bins = false;  // some layer has L_T <= 64 (8-bit words, many words per tile)
+    bool has_shifted_tiles = false;  // some tile of the larger class has skip != 0
     WorkspaceLayout ws;
     std::vector<LayerDev> layers;
     std::vector<TileDev> ctiles;
@@ -149,6 +154,7 @@ struct CompressArgs {
     uint32_t fold_scan;                 // no k_scan launch: k_place computes word offsets and layer scales itself
     uint32_t place_tiled;               // the placement is k_place_tiled: one workgroup per tile, residue corrected line by line
     uint32_t lazy;                      // k_fused applies the waiting residue corrections of the previous call
+    uint32_t shift;                     // the launch over the larger tiles uses the kernel that honours TileDev::skip
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2
     uint64_t o_stage;

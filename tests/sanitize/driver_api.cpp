@@ -39,6 +39,11 @@ static int check_plan(const std::vector<adacomp_layer_t> &t)
             if (td.n_elems == 0 || td.n_elems > cap || td.n_bins == 0 || td.n_bins > kMaxTileBins) return 104;
             if (td.n_bins != (td.n_elems + td.L_T - 1) / td.L_T) return 105;
             if (td.aligned() != (td.elem_base % 4 == 0)) return 106;
+            // a tile that keeps 16-byte accesses although it is not aligned: larger class only, skip is its
+            // misalignment, and the tile still fits its class with the misalignment added
+            if (td.skip() != 0 && (td.aligned() || td.jcode() != 1 || td.skip() != td.elem_base % 4 || td.n_elems + td.skip() > 16384u)) return 119;
+            if (td.skip() == 0 && !td.aligned() && td.jcode() == 1 && td.n_elems + td.elem_base % 4 <= 16384u) return 146;
+            if (td.skip() != 0 && !p.has_shifted_tiles) return 147;
             if (td.magic != bin_magic(td.L_T)) return 107;
             if (td.n_elems > 16384u) return 108;  // the multiply-shift bin index is checked below this
             if (td.stage_base % 4u != 0 || td.stage_base < stage_next) return 117;   // stretches do not overlap

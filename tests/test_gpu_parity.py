@@ -147,6 +147,11 @@ EDGE_TABLES = {
     "LT4096_LT4097": [("a", 3 * 4096 + 9, 4096), ("b", 3 * 4097 + 1, 4097)],
     "LT5000_LT8192": [("a", 5000 * 5 + 3, 5000), ("b", 8192 * 3, 8192)],
     "LT16384_and_odd_16383": [("a", 16384 * 3 + 5, 16384), ("b", 16383 * 2 + 7, 16383)],
+    # bin lengths whose tiles start at every 4-byte position of a 16-byte slot: odd lengths below and above
+    # 4096 (groups of four bins per tile / single unaligned bins), twice an odd number above 8192, and the
+    # two lengths whose unaligned tiles do not fit their tile class with the misalignment added
+    "odd_bin_lengths": [("a", 1025 * 13 + 3, 1025), ("b", 3001 * 9 + 2, 3001), ("c", 4097 * 9 + 5, 4097), ("d", 5001 * 7 + 1, 5001),
+                        ("e", 8194 * 5 + 3, 8194), ("f", 16381 * 5 + 2, 16381), ("g", 16382 * 4 + 1, 16382), ("h", 16383 * 5, 16383)],
     "tiny_layers": [("a", 1, 500), ("b", 2, 50), ("c", 3, 1), ("d", 5, 16384), ("e", 63, 64)],
     "many_layers_300": [(f"l{i}", 1 + (i * 37) % 211, (1, 3, 50, 64, 65, 500)[i % 6]) for i in range(300)],
     "mixed_with_gaps": [("a", 4801, 50), ("b", 102402, 50), ("c", 786433, 500), ("d", 1923, 500), ("e", 777, 9)],
@@ -575,6 +580,13 @@ def test_unpack_update_full_size_tables(H, oracle_lib):
 def test_unpack_update_edge_table(H, oracle_lib, kind):
     wl = W.custom("upd_edge", EDGE_TABLES["mixed_with_gaps"] + [("z", 16383 * 2 + 7, 16383)], dist="normal_outliers")
     _update_case(oracle_lib, wl, 3, 3, kind, False, seed=5)
+
+
+@pytest.mark.parametrize("kind,with_dense", [(1, False), (1, True), (2, True)])
+def test_unpack_update_odd_bin_lengths(H, oracle_lib, kind, with_dense):
+    """The optimizer epilogue on tiles that start at every 4-byte position of a 16-byte slot."""
+    wl = W.custom("upd_odd", EDGE_TABLES["odd_bin_lengths"], dist="normal_outliers")
+    _update_case(oracle_lib, wl, 3, 2, kind, with_dense, seed=15)
 
 
 def test_unpack_update_many_learners_and_errors(H, oracle_lib):
