@@ -19,6 +19,8 @@
 //            as (index-in-bin, ternary code) words and applies the only step that needs the
 //            layer-wide scale, residue <- G - Gq at the sent elements (a read-modify-write of
 //            about 0.3-10 % of the elements); one extra workgroup writes header and records.
+//            Large tables with short bins (L_T <= 64), which send several percent of their elements,
+//            use k_place_tiled instead: a workgroup per tile, the residue corrected line by line.
 // adacomp_compress_batch_lazy runs the same three, but k_place leaves that read-modify-write out
 // and the next call's k_fused applies the corrections to the residue values while it has them in
 // registers (same arithmetic, same results; adacomp_residue_sync writes them on request).
