@@ -753,12 +753,23 @@ def test_subnormal_and_large_magnitudes(H, oracle_lib):
     _update_case(oracle_lib, wl, 3, 2, 2, False, grads_fn=grads)
 
 
-def test_non_finite_inputs_are_memory_safe(H):
+@pytest.mark.parametrize("fold", [True, False])
+def test_non_finite_inputs_are_memory_safe(H, fold):
     """NaN and infinities are outside the method (the results are unspecified), but the calls stay
     inside their buffers: the packet is a well-formed container no longer than the bound, nothing is
-    written behind it or outside the layers, and the packet can be unpacked."""
+    written behind it or outside the layers, and the packet can be unpacked.  With the folded scan and
+    with the separate scan launch (tile-by-tile placement for this table's short bins)."""
     import gpu_harness as G
     import packet_format as pf
+    import paper_1712_02679_amd as A
+    A.adacomp_tuning_fold_scan(fold)
+    try:
+        _non_finite_case(G, pf)
+    finally:
+        A.adacomp_tuning_fold_scan(True)
+
+
+def _non_finite_case(G, pf):
     wl = W.custom("nonfinite", [("a", 50 * 90 + 7, 50), ("b", 500 * 20 + 11, 500), ("c", 16384 + 9, 16384)], dist="normal_outliers")
     table, n = wl.table(), wl.n_total
     mask = G.layer_mask(table, n)
@@ -819,12 +830,23 @@ def test_all_selected_every_bin_length(H, oracle_lib, batch):
     assert stats[0][3] == A.adacomp_packet_bound(wl.table())
 
 
-def test_truncated_packet(H, oracle_lib):
+@pytest.mark.parametrize("fold", [True, False])
+def test_truncated_packet(H, oracle_lib, fold):
     """Capacity below the need: status = truncated, total_bytes = the need, the words that fit are
-    the oracle's, nothing is written past the capacity, residue updated as if all had been sent."""
+    the oracle's, nothing is written past the capacity, residue updated as if all had been sent.
+    With the folded scan (word-by-word placement) and with the separate scan launch, where this
+    table's short bins take the tile-by-tile placement."""
     import gpu_harness as G
     import packet_format as pf
     import paper_1712_02679_amd as A
+    A.adacomp_tuning_fold_scan(fold)
+    try:
+        _truncated_packet_case(oracle_lib, G, pf, A)
+    finally:
+        A.adacomp_tuning_fold_scan(True)
+
+
+def _truncated_packet_case(oracle_lib, G, pf, A):
     wl = W.custom("trunc", [("a", 50 * 200, 50), ("b", 500 * 100, 500)])
     table, n = wl.table(), wl.n_total
     g = W.gradient(wl, 0, 0)
