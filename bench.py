@@ -13,7 +13,9 @@ Prints ONE JSON line.  `value` = bytes of float32 gradient compressed and unpack
 (n_learners * 4 * n_elems per step).  `roofline` prices the dominant kernel (k_fused, the
 streaming pass of compress) by its algorithmic bytes, 12 per element (read dW, read residue,
 write residue), against the MI355X's 8 TB/s HBM peak, with its duration measured by HIP events
-on the launch stream inside the timed region.  `cpu_baseline` times the CPU oracle, as it stands,
+on the launch stream inside the timed region; beside the published peak the line carries what this
+GPU sustains on a bare in-place triad and a bare fill with the same access pattern
+(`device_triad_GBs`, `device_fill_GBs`), measured in the same run.  `cpu_baseline` times the CPU oracle, as it stands,
 on a bounded sample of the same workload; `parity_checked` says whether step 0 of the calls that
 were timed gave, bit for bit, the packets, residues and dense sum that oracle run produced (the
 run exits non-zero if not); `per_config` holds the other four configurations, each as configured.
@@ -223,6 +225,20 @@ def main():
     c1.record()
     torch.cuda.synchronize()
     copy_gbs = 8.0 * n_total * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    # the two streaming ceilings of this GPU with the access pattern of the hot kernels and nothing
+    # else: an in-place x <- x + y (12 B per element, what k_fused moves) and a fill (4 B per element,
+    # what the dense sum writes); `dense` is scratch here, unpack overwrites it
+    n4 = n_total // 4 * 4
+    ceilings = {}
+    for name, call, bytes_per_elem in (("triad", lambda: A.adacomp_triad_f32(dense, grads[0], n4), 12.0),
+                                       ("fill", lambda: A.adacomp_fill_f32(dense, 0.0, n4), 4.0)):
+        call()
+        c0.record()
+        for _ in range(5):
+            call()
+        c1.record()
+        torch.cuda.synchronize()
+        ceilings[name] = bytes_per_elem * n4 * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
 
     # ---- warm-up on the same buffers, then residues back to zero (training start) ---------------
     for t in range(Wm):
@@ -307,7 +323,8 @@ def main():
                     "traffic": (measured_traffic(wl.name) or 0) * per_launch or None,
                     "traffic_source": "committed rocprofv3 --pmc summary profiles/k_fused_hbm_traffic.txt (not a counter of this run)",
                     "algorithmic_bytes_per_launch": alg_bytes_launch, "learners_per_launch": per_launch,
-                    "avg_launch_ms": round(dur_ms, 5), "launches": int(fused_n)}
+                    "avg_launch_ms": round(dur_ms, 5), "launches": int(fused_n),
+                    "frac_of_measured_triad": round(achieved / ceilings["triad"], 4)}
     # whole step by algorithmic bytes: n * (12 N + P) + 4 N + n * P
     step_alg_bytes = n_learners * (12 * n_params + packet_bytes_mean) + 4 * n_params + n_learners * packet_bytes_mean
     step_frac = step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
@@ -467,6 +484,7 @@ def main():
         "parity_checked": parity,
         "per_config": per_config,
         "hbm_frac_step_algorithmic": round(step_frac, 4), "device_copy_GBs": round(copy_gbs, 1),
+        "device_triad_GBs": round(ceilings["triad"], 1), "device_fill_GBs": round(ceilings["fill"], 1),
         "compress_ms_per_step": None if graph is not None else round(compress_ms, 4),
         "unpack_ms_per_step": None if graph is not None else round(unpack_ms, 4),
         "unpack_update": upd,

@@ -31,6 +31,14 @@ int adacomp_workspace_gmax(const adacomp_layer_t *layers, uint32_t n_layers, siz
  * which HBM byte counters and the achievable copy bandwidth are calibrated. */
 int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
 
+/* The two streaming ceilings the hot kernels are measured against, with the access pattern of the
+ * streaming pass of compress and nothing else (tiles of 4096 elements, 16 per thread, streaming
+ * 16-byte loads and stores, the same tile order): x <- x + y in place, 12 bytes per element as
+ * pack() moves (read dW, read residue, write residue); and x <- value, 4 bytes per element as the
+ * dense sum of unpack() writes.  x, y 16-byte aligned and distinct, n a multiple of 4. */
+int adacomp_triad_f32(float *x, const float *y, size_t n, void *hip_stream);
+int adacomp_fill_f32(float *x, float value, size_t n, void *hip_stream);
+
 /* Host-only exhaustive check of the multiply-shift constants the kernels use to turn an element
  * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */
 int adacomp_selftest_binindex(void);

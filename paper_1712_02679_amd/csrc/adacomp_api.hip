@@ -815,6 +815,22 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream)
     return n == 0 ? ADACOMP_OK : launch_copy(dst, src, n, hip_stream);
 }
 
+int adacomp_triad_f32(float *x, const float *y, size_t n, void *hip_stream)
+{
+    if (!x || !y || x == y) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16 || n % 4 != 0) return ADACOMP_EALIGN;
+    if (n >= (size_t(1) << 43)) return ADACOMP_EINVAL;
+    return n == 0 ? ADACOMP_OK : launch_triad(x, y, n, hip_stream);
+}
+
+int adacomp_fill_f32(float *x, float value, size_t n, void *hip_stream)
+{
+    if (!x) return ADACOMP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || n % 4 != 0) return ADACOMP_EALIGN;
+    if (n >= (size_t(1) << 43)) return ADACOMP_EINVAL;
+    return n == 0 ? ADACOMP_OK : launch_fill(x, value, n, hip_stream);
+}
+
 int adacomp_selftest_binindex(void)
 {
     for (uint32_t T = 2; T <= ADACOMP_LT_MAX; ++T) {

@@ -1223,3 +1223,24 @@ def test_copy_kernel(H):
         A.adacomp_copy_f32(dst, src, n)
         torch.cuda.synchronize()
         assert torch.equal(dst[:n], src) and torch.all(dst[n:] == -1.0)
+
+
+def test_calibration_kernels(H):
+    """The bare triad and fill that bench.py measures the hot kernels against do what they say
+    (x <- x + y as single float32 additions, x <- value), on whole and ragged numbers of tiles, and
+    touch nothing beyond n."""
+    import paper_1712_02679_amd as A
+    for n in (4, 4096, 4096 * 64, 4096 * 130 + 8, (1 << 22) + 4092):
+        x0 = torch.randn(n + 8, dtype=torch.float32, device="cuda:0")
+        y = torch.randn(n + 8, dtype=torch.float32, device="cuda:0")
+        x = x0.clone()
+        A.adacomp_triad_f32(x, y, n)
+        torch.cuda.synchronize()
+        assert torch.equal(x[:n], x0[:n] + y[:n]) and torch.equal(x[n:], x0[n:])
+        A.adacomp_fill_f32(x, 2.5, n)
+        torch.cuda.synchronize()
+        assert torch.all(x[:n] == 2.5) and torch.equal(x[n:], x0[n:])
+    with pytest.raises(A.AdacompError):
+        A.adacomp_triad_f32(x, y, 6)          # not a multiple of 4
+    with pytest.raises(A.AdacompError):
+        A.adacomp_triad_f32(x, x, 8)          # in place on itself
