@@ -38,6 +38,10 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream);
  * dense sum of unpack() writes.  x, y 16-byte aligned and distinct, n a multiple of 4. */
 int adacomp_triad_f32(float *x, const float *y, size_t n, void *hip_stream);
 int adacomp_fill_f32(float *x, float value, size_t n, void *hip_stream);
+/* The same triad with at most workgroups_per_cu (3 .. 8; adacomp_triad_f32 is 8) workgroups resident on
+ * a compute unit: HBM serves this access pattern better with fewer bytes in flight, so the ceiling a
+ * kernel is held against is the best of these, not the full-residency one. */
+int adacomp_triad_resident_f32(float *x, const float *y, size_t n, uint32_t workgroups_per_cu, void *hip_stream);
 
 /* Host-only exhaustive check of the multiply-shift constants the kernels use to turn an element
  * index into a bin index (every L_T in 1..16384 against every index below 16384). 0 if all agree. */

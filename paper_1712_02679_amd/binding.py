@@ -24,7 +24,7 @@ EXPORTS = [
     "adacomp_compress", "adacomp_compress_static", "adacomp_compress_batch", "adacomp_compress_variant",
     "adacomp_compress_batch_lazy", "adacomp_residue_sync",
     "adacomp_unpack_accumulate", "adacomp_unpack_update", "adacomp_strerror", "adacomp_workspace_gmax", "adacomp_debug_keep_gmax",
-    "adacomp_copy_f32", "adacomp_triad_f32", "adacomp_fill_f32",
+    "adacomp_copy_f32", "adacomp_triad_f32", "adacomp_triad_resident_f32", "adacomp_fill_f32",
     "adacomp_selftest_binindex", "adacomp_tuning_unpack_min_groups", "adacomp_tuning_fold_scan", "adacomp_tuning_place_tiled", "adacomp_timing_enable", "adacomp_timing_read",
 ]
 
@@ -95,6 +95,7 @@ def lib():
         L.adacomp_debug_keep_gmax.argtypes = [ctypes.c_int]
         L.adacomp_copy_f32.argtypes = [vp, vp, sz, vp]
         L.adacomp_triad_f32.argtypes = [vp, vp, sz, vp]
+        L.adacomp_triad_resident_f32.argtypes = [vp, vp, sz, ctypes.c_uint32, vp]
         L.adacomp_fill_f32.argtypes = [vp, ctypes.c_float, sz, vp]
         L.adacomp_tuning_unpack_min_groups.argtypes = [ctypes.c_uint32]
         L.adacomp_tuning_fold_scan.argtypes = [ctypes.c_int]
@@ -260,6 +261,12 @@ def adacomp_copy_f32(dst, src, n=None):
 def adacomp_triad_f32(x, y, n=None):
     """x <- x + y in place with the access pattern of the streaming pass of compress (12 B per element)."""
     _check(lib().adacomp_triad_f32(_ptr(x), _ptr(y), x.numel() if n is None else int(n), _stream()))
+
+
+def adacomp_triad_resident_f32(x, y, workgroups_per_cu, n=None):
+    """The same triad with at most workgroups_per_cu (3 .. 8) workgroups resident per compute unit."""
+    _check(lib().adacomp_triad_resident_f32(_ptr(x), _ptr(y), x.numel() if n is None else int(n),
+                                            int(workgroups_per_cu), _stream()))
 
 
 def adacomp_fill_f32(x, value=0.0, n=None):

@@ -815,12 +815,17 @@ int adacomp_copy_f32(float *dst, const float *src, size_t n, void *hip_stream)
     return n == 0 ? ADACOMP_OK : launch_copy(dst, src, n, hip_stream);
 }
 
-int adacomp_triad_f32(float *x, const float *y, size_t n, void *hip_stream)
+int adacomp_triad_resident_f32(float *x, const float *y, size_t n, uint32_t workgroups_per_cu, void *hip_stream)
 {
-    if (!x || !y || x == y) return ADACOMP_EINVAL;
+    if (!x || !y || x == y || workgroups_per_cu < 3 || workgroups_per_cu > 8) return ADACOMP_EINVAL;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16 || n % 4 != 0) return ADACOMP_EALIGN;
     if (n >= (size_t(1) << 43)) return ADACOMP_EINVAL;
-    return n == 0 ? ADACOMP_OK : launch_triad(x, y, n, hip_stream);
+    return n == 0 ? ADACOMP_OK : launch_triad(x, y, n, workgroups_per_cu, hip_stream);
+}
+
+int adacomp_triad_f32(float *x, const float *y, size_t n, void *hip_stream)
+{
+    return adacomp_triad_resident_f32(x, y, n, 8, hip_stream);
 }
 
 int adacomp_fill_f32(float *x, float value, size_t n, void *hip_stream)

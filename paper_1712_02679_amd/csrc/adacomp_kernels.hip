@@ -1390,10 +1390,13 @@ int launch_unpack(const UnpackArgs &a, int kind, void *stream)
     return check_launch();
 }
 
-int launch_triad(float *x, const float *y, size_t n, void *stream)
+int launch_triad(float *x, const float *y, size_t n, uint32_t resident, void *stream)
 {
     const uint32_t n_tiles = uint32_t((n + 4095u) / 4096u);
-    hipLaunchKernelGGL(k_triad, dim3(n_tiles), dim3(kWG), 0, static_cast<hipStream_t>(stream), x, y, n_tiles, n);
+    // fewer than 8 workgroups per compute unit: each asks for dynamic LDS it never touches, sized so that
+    // `resident` of them fit the 160 KB of a compute unit and one more does not
+    const uint32_t idle_lds = resident >= 8u ? 0u : 163840u / resident - 1024u;
+    hipLaunchKernelGGL(k_triad, dim3(n_tiles), dim3(kWG), idle_lds, static_cast<hipStream_t>(stream), x, y, n_tiles, n);
     return check_launch();
 }
 

@@ -188,7 +188,7 @@ int launch_place(const CompressArgs &a, void *stream);
 constexpr uint32_t kPlaceEager = 0, kPlaceWords = 1, kPlaceResidue = 2;
 int launch_unpack(const UnpackArgs &a, int kind, void *stream);  // kind 0: 16-bit words, 1: 8-bit, 2: both
 int launch_copy(float *dst, const float *src, size_t n, void *stream);
-int launch_triad(float *x, const float *y, size_t n, void *stream);   // n a multiple of 4, below 2^44
+int launch_triad(float *x, const float *y, size_t n, uint32_t resident, void *stream);   // n a multiple of 4, below 2^44; resident 3 .. 8
 int launch_fill(float *x, float value, size_t n, void *stream);
 
 }  // namespace adacomp

@@ -1237,6 +1237,11 @@ def test_calibration_kernels(H):
         A.adacomp_triad_f32(x, y, n)
         torch.cuda.synchronize()
         assert torch.equal(x[:n], x0[:n] + y[:n]) and torch.equal(x[n:], x0[n:])
+        for resident in (3, 4, 6, 8):       # the same kernel with fewer workgroups per compute unit
+            x.copy_(x0)
+            A.adacomp_triad_resident_f32(x, y, resident, n)
+            torch.cuda.synchronize()
+            assert torch.equal(x[:n], x0[:n] + y[:n]) and torch.equal(x[n:], x0[n:])
         A.adacomp_fill_f32(x, 2.5, n)
         torch.cuda.synchronize()
         assert torch.all(x[:n] == 2.5) and torch.equal(x[n:], x0[n:])
@@ -1244,3 +1249,6 @@ def test_calibration_kernels(H):
         A.adacomp_triad_f32(x, y, 6)          # not a multiple of 4
     with pytest.raises(A.AdacompError):
         A.adacomp_triad_f32(x, x, 8)          # in place on itself
+    for resident in (0, 2, 9):
+        with pytest.raises(A.AdacompError):
+            A.adacomp_triad_resident_f32(x, y, resident, 8)
