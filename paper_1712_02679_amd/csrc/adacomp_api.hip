@@ -517,6 +517,7 @@ static int compress_common(const adacomp_layer_t *layers, uint32_t n_layers, uin
     // more before its first store and loses more at every launch boundary: two learners per launch
     // (or four) are 1.5 % faster per step there, and 0.3 % (1 %) slower on the eager path.
     const uint32_t per_launch_max = p.n_elems_total >= kSplitElems ? (lazy ? 2u : 1u) : kMaxBatch;
+    a.fused_idle_lds = (per_launch_max == 1u && n_learners >= kFusedIdleMinLearners) ? kFusedIdleLds : 0u;
     auto enqueue = [&]() -> int {
     int rc = ADACOMP_OK;
     for (uint32_t done = 0; done < n_learners; done += kMaxBatch) {

@@ -143,9 +143,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     if (pos < (a.class_count & ~63u)) pos = (pos & ~63u) | ((pos & 7u) << 3) | ((pos >> 3) & 7u);
     const uint32_t tile = a.class_tiles ? a.class_tiles[a.class_first + pos] : pos;
     const TileDev td = a.tiles[tile];
-    // the layer's record is needed only at the end, for the tile's outputs, but it is fetched now: a
-    // dependent load there would add its whole latency to the life of the workgroup
-    const LayerDev ld = a.layers[td.layer()];
+    // The layer's record is needed only at the end, for the tile's outputs.  The 256-thread kernel
+    // fetches it now: a dependent load in the tail adds its whole latency to the life of the workgroup
+    // (which pays once fewer workgroups are resident, see the launcher).  The 1024-thread kernel
+    // fetches it where it is used: with the early fetch its launches took a third longer (bins of
+    // 5000 elements: 273 -> 362 us per 125 M elements).
+    LayerDev ld;
+    if (WAVES == 4) ld = a.layers[td.layer()];
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
     TileOut *const tile_out = reinterpret_cast<TileOut *>(sb + a.o_tile_out);
     float *const gmax_out = reinterpret_cast<float *>(sb + a.o_gmax);
@@ -367,6 +371,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     __syncthreads();
 
     // ---- tile outputs: counts (into the packet), g_max, sum of g_max, chunk prefixes, total ----
+    if (WAVES != 4) ld = a.layers[td.layer()];
     if (ld.word_bytes == 1u) {
         uint8_t *cp = packet + ld.counts_offset + td.first_bin;
         for (uint32_t i = tid; i < nb; i += WG) cp[i] = uint8_t(s_cnt[i]);
@@ -1301,16 +1306,8 @@ __global__ __launch_bounds__(kWG) void k_fill(float *__restrict__ x, float value
 // ---- launchers ---------------------------------------------------------------------------------
 static int check_launch() { return hipGetLastError() == hipSuccess ? ADACOMP_OK : ADACOMP_EHIP; }
 
-// Dynamic LDS that no kernel touches, asked for with the launches of the 256-thread streaming kernel:
-// with its 8.5 KB of arrays that leaves room for 6 workgroups per compute unit instead of the 8 its
-// registers allow.  The kernel is bound by HBM, and HBM serves it better with fewer bytes in flight
-// (a bare triad of the same shape gains 1-10 % from 6 down to 3 resident workgroups); since the layer
-// record is fetched at the start of a workgroup and not in its tail, 6 workgroups still cover the
-// LDS phases: 16 learners x 125 M elements take 4.08 ms against 4.15 (7: 4.23, 5: 4.18; with the
-// fetch in the tail 6 took 4.41).  The kernel that first applies waiting corrections is longer per
-// tile and loses with any cap (4.02 -> 4.04 / 4.21 / 5.14 ms with 7 / 6 / 5), so it gets none.
-constexpr uint32_t kFusedIdleLds = 18000;
-
+// a.fused_idle_lds: dynamic LDS that no kernel touches, asked for with the launches of the eager
+// 256-thread kernel (the host decides when, adacomp_plan.h says why).
 int launch_fused(const CompressArgs &a, int jcode, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1324,11 +1321,11 @@ int launch_fused(const CompressArgs &a, int jcode, void *stream)
         if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<4, 16, false, true>), grid, wg, 0, s, a);
     } else if (!variant) {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, false>), grid, wg, kFusedIdleLds, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, false, false>), grid, wg, a.fused_idle_lds, s, a);
         else if (a.shift) hipLaunchKernelGGL((k_fused<4, 16, false, false, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<4, 16, false, false>), grid, wg, 0, s, a);
     } else {
-        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, true, false>), grid, wg, kFusedIdleLds, s, a);
+        if (jcode == 0) hipLaunchKernelGGL((k_fused<4, 4, true, false>), grid, wg, a.fused_idle_lds, s, a);
         else if (a.shift) hipLaunchKernelGGL((k_fused<4, 16, true, false, true>), grid, wg, 0, s, a);
         else hipLaunchKernelGGL((k_fused<4, 16, true, false>), grid, wg, 0, s, a);
     }

@@ -139,6 +139,19 @@ int find_plan(const adacomp_layer_t *layers, uint32_t n_layers, const void *work
 constexpr uint32_t kMaxBatch = 32;  // learners per launch of the compress kernels
 constexpr uint64_t kSplitElems = 32u * 1000u * 1000u;  // gradients at least this long: one k_fused launch per learner
 
+// Dynamic LDS that no kernel touches, asked for with the launches of the eager 256-thread streaming
+// kernel in calls that launch it once per learner, for many learners: with its 8.5 KB of arrays that leaves room for 6 workgroups per
+// compute unit instead of the 8 its registers allow.  The kernel is bound by HBM, and HBM serves it
+// better with fewer bytes in flight (a bare triad of the same shape gains up to 7 % between 8 and 4
+// resident workgroups); since the layer record is fetched at the start of a workgroup and not in its
+// tail, 6 workgroups still cover the LDS phases.  Measured per learner of the 125 M-element table,
+// uncapped / capped: 235.5 / 247.9 us in calls of 1 learner, 243.3 / 251.2 of 2, 240.2 / 245.9 of 4,
+// 242.1 / 239.0 of 8, 242.4 / 237.3 of 12, 243.8 / 238.0 of 16: a launch that follows another
+// streaming launch gains, one that follows a placement and an unpack loses, hence the learner count.
+// The kernel that first applies waiting corrections is longer per tile and loses with any cap.
+constexpr uint32_t kFusedIdleLds = 18000;
+constexpr uint32_t kFusedIdleMinLearners = 8;
+
 struct CompressArgs {
     const TileDev *tiles;
     const LayerDev *layers;
@@ -155,6 +168,7 @@ struct CompressArgs {
     uint32_t place_tiled;               // the placement is k_place_tiled: one workgroup per tile, residue corrected line by line
     uint32_t lazy;                      // k_fused applies the waiting residue corrections of the previous call
     uint32_t shift;                     // the launch over the larger tiles uses the kernel that honours TileDev::skip
+    uint32_t fused_idle_lds;            // bytes of dynamic LDS for the eager 256-thread k_fused launches (kFusedIdleLds or 0)
     uint32_t rule;                      // ADACOMP_RULE_*
     float soft_factor_minus_1;          // 1 for the paper's factor 2
     uint64_t o_stage;
