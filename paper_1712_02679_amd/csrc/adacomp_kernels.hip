@@ -1280,16 +1280,24 @@ __global__ __launch_bounds__(kWG) void k_triad(float *__restrict__ x, const floa
     uint32_t tile = blockIdx.x;
     if (tile < (n_tiles & ~63u)) tile = (tile & ~63u) | ((tile & 7u) << 3) | ((tile >> 3) & 7u);
     const size_t base = size_t(tile) * 4096u;
-    vfloat4 a[4], b[4];
+    if (base + 4096u <= n) {   // a whole tile: eight loads in flight per thread, no branch between them
+        vfloat4 a[4], b[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const size_t e = base + (uint32_t(j) * kWG + threadIdx.x) * 4u;
-        if (e + 4u <= n) { a[j] = load_stream4(x + e); b[j] = load_stream4(y + e); }
+        for (int j = 0; j < 4; ++j) {
+            const size_t e = base + (uint32_t(j) * kWG + threadIdx.x) * 4u;
+            a[j] = load_stream4(x + e);
+            b[j] = load_stream4(y + e);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t e = base + (uint32_t(j) * kWG + threadIdx.x) * 4u;
+            store_stream4(x + e, a[j] + b[j]);
+        }
+        return;
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 4; ++j) {   // the ragged last tile
         const size_t e = base + (uint32_t(j) * kWG + threadIdx.x) * 4u;
-        if (e + 4u <= n) store_stream4(x + e, a[j] + b[j]);
+        if (e + 4u <= n) store_stream4(x + e, load_stream4(x + e) + load_stream4(y + e));
     }
 }
 
