@@ -143,11 +143,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     if (pos < (a.class_count & ~63u)) pos = (pos & ~63u) | ((pos & 7u) << 3) | ((pos >> 3) & 7u);
     const uint32_t tile = a.class_tiles ? a.class_tiles[a.class_first + pos] : pos;
     const TileDev td = a.tiles[tile];
-    // The layer's record is needed only at the end, for the tile's outputs.  The 256-thread kernel
-    // fetches it now: a dependent load in the tail adds its whole latency to the life of the workgroup
-    // (which pays once fewer workgroups are resident, see the launcher).  The 1024-thread kernel
-    // fetches it where it is used: with the early fetch its launches took a third longer (bins of
-    // 5000 elements: 273 -> 362 us per 125 M elements).
+    // The layer's record is needed only at the end, for the tile's outputs, but a dependent load in
+    // the tail adds its whole latency to the life of the workgroup, so it is fetched early.  The
+    // 256-thread kernel fetches it here, which holds its streaming loads back until the record is in
+    // (they wait for the same counter as the buffer pointers); measured, that is as fast or faster
+    // than the fetch behind the loads.  The 1024-thread kernel, of which a compute unit holds two
+    // workgroups, cannot hide that wait (a third longer per launch) and fetches behind its loads
+    // (2-4 % faster than in the tail).
     LayerDev ld;
     if (WAVES == 4) ld = a.layers[td.layer()];
     uint8_t *const sb = a.scratch + uint64_t(lr) * a.scratch_stride;
@@ -193,6 +195,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
             }
         }
     }
+    if (WAVES != 4) ld = a.layers[td.layer()];
     if (LAZY) {
         // The previous call left, for this tile, its staged entries (tile-local index, sign), their
         // number and the layer's scale.  An entry becomes a code byte in LDS at the element's place;
@@ -371,7 +374,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_fused(const CompressArgs a)
     __syncthreads();
 
     // ---- tile outputs: counts (into the packet), g_max, sum of g_max, chunk prefixes, total ----
-    if (WAVES != 4) ld = a.layers[td.layer()];
     if (ld.word_bytes == 1u) {
         uint8_t *cp = packet + ld.counts_offset + td.first_bin;
         for (uint32_t i = tid; i < nb; i += WG) cp[i] = uint8_t(s_cnt[i]);
