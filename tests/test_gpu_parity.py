@@ -462,6 +462,16 @@ def test_lazy_bookkeeping(H, oracle_lib):
         eager.close()
 
 
+def test_variant_workload5_eight_learners(H, oracle_lib):
+    """The selection variants at the size and learner count where the streaming kernel is launched
+    once per learner with fewer workgroups resident per compute unit: 8 learners of the 125 M-element
+    table, one step, soft-threshold factor 2.5, every packet, residue and the sum against the oracle."""
+    wl = W.workload(5)
+    stats = H.run_parity(oracle_lib, wl, 8, 1, batch=True, rule=0, soft_factor=2.5, check_gmax=False,
+                         threads=16, oracle_threads=8, label="variant factor 2.5 at full size")
+    assert all(s[2] > 0 for s in stats)
+
+
 @pytest.mark.parametrize("rule,factor", [(1, 2.0), (2, 2.0), (0, 1.5), (0, 3.0), (0, 1.0), (1, 2.5), (0, 2.75)])
 def test_variants_workload2(H, oracle_lib, rule, factor):
     wl = W.workload(2)
